@@ -1,0 +1,194 @@
+/*
+ * libleann -- C ABI of the MI355X (gfx950) implementation of LEANN's search hot
+ * path (arXiv 2506.08276): the recompute-and-score loop of best-first
+ * proximity-graph search.
+ *
+ * Conventions that hold for every call
+ *   - "dev" pointers are device (HBM) addresses on the context's GPU, "host"
+ *     pointers are ordinary host memory.  All buffers are caller-owned and
+ *     only borrowed for the duration of the call; the library owns the opaque
+ *     handles (leann_ctx, leann_pq) and its internal workspaces.
+ *   - Work is enqueued on the HIP stream given to leann_create.  Calls that
+ *     write host memory or return counts synchronise that stream; the others
+ *     return as soon as the work is enqueued.
+ *   - Every function returns LEANN_OK (0) or a negative status; on error no
+ *     output buffer has been written.  leann_last_error() gives a message for
+ *     the calling thread.  Nothing is printed and nothing aborts.
+ *   - Arrays are row-major.  Scores are inner-product similarities: larger is
+ *     closer.  Every ranking uses the total order (score descending, id
+ *     ascending).
+ */
+#ifndef LEANN_H
+#define LEANN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    LEANN_OK = 0,
+    LEANN_EINVAL = -1,    /* bad argument value (k > ef, ratio outside (0,1], null pointer, ...) */
+    LEANN_ENOMEM = -2,    /* device or host allocation failed */
+    LEANN_EDEVICE = -3,   /* a HIP call failed */
+    LEANN_ESHAPE = -4,    /* shape the kernels do not cover (see leann_create) or inconsistent sizes */
+    LEANN_ECAPACITY = -5  /* a per-query queue outgrew its capacity */
+};
+
+enum { LEANN_F32 = 0, LEANN_BF16 = 1 };
+
+typedef struct leann_ctx leann_ctx;
+typedef struct leann_pq leann_pq;
+
+/* Encoder shape.  The paper fixes a BERT-style encoder of 110 M parameters with
+ * 768-d output over 256-token chunks (Sec. 7 set-up); the layer equations are the
+ * standard post-LN ones, see leann_embed. */
+typedef struct {
+    int32_t layers, hidden, heads, ffn, vocab, max_pos;
+    float ln_eps;
+} leann_encoder_desc;
+
+/* Pruned proximity graph in CSR form, 4-byte neighbour ids (Sec. 5, "Space(G1)").
+ * row_ptr[n+1] and col_idx[row_ptr[n]] are device pointers; entry is the fixed
+ * entry point p of Algorithm 2. */
+typedef struct {
+    const uint64_t *row_ptr;
+    const uint32_t *col_idx;
+    int64_t n;
+    uint32_t entry;
+} leann_graph;
+
+/* Raw chunk store as token ids: tokens[n][seq] (PAD beyond the valid length,
+ * content ignored) and lengths[n] in [1, seq]; device pointers. */
+typedef struct {
+    const int32_t *tokens;
+    const int32_t *lengths;
+    int64_t n;
+    int32_t seq;
+} leann_chunks;
+
+/* Optional table of stored exact embeddings (the paper's embedding cache for
+ * frequently visited nodes, Sec. 3 / App. D "Relaxing Disk Constraint").
+ * slot_of[n] gives the row of emb for a node, or -1 when the node must be
+ * recomputed; emb[rows][d] fp32.  Device pointers.  NULL = recompute everything. */
+typedef struct {
+    const int32_t *slot_of;
+    const float *emb;
+    int64_t rows;
+} leann_emb_cache;
+
+/* Per-call totals over all queries of a leann_search call. */
+typedef struct {
+    int64_t hops;              /* exploration steps (Alg. 2 "read the closest unvisited node") */
+    int64_t adc_candidates;    /* neighbours scored with PQ */
+    int64_t recomputed_chunks; /* exact scores taken (sum over queries, entry point included) */
+    int64_t encoded_chunks;    /* chunks actually sent through the encoder (after sharing within a round) */
+    int64_t encoded_tokens;    /* valid tokens of those chunks */
+    int64_t flushes;           /* per-query batch flushes */
+    int64_t rounds;            /* traverse -> encode -> insert rounds over the whole query set */
+    float encoder_ms, traverse_ms, total_ms; /* device time (HIP events) */
+} leann_search_stats;
+
+const char *leann_last_error(void);
+
+/*
+ * Create a context holding the encoder weights.
+ *   weights_dev: packed parameters on the device, dtype LEANN_F32 or LEANN_BF16
+ *   (every value in that one type), in this order, linear maps stored [out][in]:
+ *     tok_emb[vocab][d], pos_emb[max_pos][d], seg_emb[d], emb_ln_g[d], emb_ln_b[d],
+ *     per layer: Wqkv[3d][d] (query rows, key rows, value rows), bqkv[3d], Wo[d][d], bo[d],
+ *                ln1_g[d], ln1_b[d], W1[F][d], b1[F], W2[d][F], b2[d], ln2_g[d], ln2_b[d].
+ *   The library keeps its own copy (matrices and embedding tables in bf16, the
+ *   rest in fp32); the caller may free weights_dev after the call returns.
+ *   Shapes covered: hidden/heads == 64, hidden % 128 == 0, ffn % 128 == 0,
+ *   sequence length <= 256; anything else is LEANN_ESHAPE.
+ *   device: HIP device ordinal; hip_stream: a hipStream_t (NULL = default stream).
+ */
+int leann_create(leann_ctx **out, const leann_encoder_desc *desc, const void *weights_dev, int weight_dtype,
+                 int device, void *hip_stream);
+void leann_destroy(leann_ctx *ctx);
+
+/*
+ * Embedding recomputation (Alg. 2 "Recompute embedding x_c"; Sec. 3 online stage).
+ * For each requested chunk: x = LN(tok_emb[id_t] + pos_emb[t] + seg_emb), t < L;
+ * per layer  x = LN(x + MHA(x) Wo + bo),  x = LN(x + GELU(x W1 + b1) W2 + b2)
+ * with softmax over the L valid keys only; e = mean_t x_t;  e <- e / max(|e|, 1e-12).
+ * bf16 matrix products with fp32 accumulation; softmax, LayerNorm and pooling in fp32.
+ *   ids_dev: int64[n_ids] chunk numbers (device), NULL = chunks 0..n_ids-1.
+ *   out_emb_dev: fp32[n_ids][hidden].
+ * A chunk's embedding does not depend on which other chunks share the call.
+ * Errors: token id outside [0, vocab), length outside [1, seq], id outside [0, n) -> LEANN_EINVAL.
+ */
+int leann_embed(leann_ctx *ctx, const leann_chunks *chunks, const int64_t *ids_dev, int64_t n_ids,
+                float *out_emb_dev);
+
+/*
+ * Build the PQ table (Sec. 3 offline stage: "builds a lightweight PQ table").
+ * Splits d into m_sub contiguous sub-vectors; per subspace runs `iters` Lloyd
+ * iterations with 256 centroids on min(n, 65536) rows chosen by a seeded
+ * permutation (splitmix64 Fisher-Yates; the first 256 rows of it are the initial
+ * centroids; an empty cluster keeps its centroid; ties go to the lowest index),
+ * then encodes all n rows.  emb_dev: fp32[n][d].  d/m_sub <= 32.
+ */
+int leann_build_pq(leann_ctx *ctx, const float *emb_dev, int64_t n, int32_t d, int32_t m_sub, int32_t iters,
+                   uint64_t seed, leann_pq **out);
+/* Copy codebook fp32[m_sub][256][d/m_sub] and codes u8[n][m_sub] to host buffers (either may be NULL). */
+int leann_pq_export(leann_ctx *ctx, const leann_pq *pq, float *codebook_host, uint8_t *codes_host);
+/* Make a PQ table from host copies of a codebook and codes. */
+int leann_pq_import(leann_ctx *ctx, const float *codebook_host, const uint8_t *codes_host, int64_t n, int32_t d,
+                    int32_t m_sub, leann_pq **out);
+/* Wrap a device-resident code table without copying it: codes_dev u8[n][m_sub] stays caller-owned and must
+ * outlive the handle; the codebook is copied from the host. */
+int leann_pq_wrap(leann_ctx *ctx, const float *codebook_host, const uint8_t *codes_dev, int64_t n, int32_t d,
+                  int32_t m_sub, leann_pq **out);
+int leann_pq_info(const leann_pq *pq, int64_t *n, int32_t *d, int32_t *m_sub);
+void leann_pq_free(leann_pq *pq);
+
+/*
+ * Approximate scores (Alg. 2 "Insert (v, Dist(q, x~_v)) into AQ"): for each query
+ * a lookup table lut[m][c] = <q_m, codebook[m][c]> is built (sub-vector summed in
+ * index order) and out[i][j] = sum_m lut[m][codes[cand[i][j]][m]] in the fixed order
+ * m = 0..m_sub-1, fp32.
+ *   queries_dev fp32[nq][d]; cand_ids_dev u32[nq][nc]; out_dev fp32[nq][nc].
+ * Candidate ids >= n are an error (LEANN_EINVAL, reported after the kernel ran; out_dev
+ * then holds -inf at those positions).
+ */
+int leann_adc(leann_ctx *ctx, const float *queries_dev, int64_t nq, const leann_pq *pq,
+              const uint32_t *cand_ids_dev, int32_t nc, float *out_dev);
+
+/*
+ * Two-level search with dynamic batching (Algorithm 2, Sec. 4.1-4.2) for nq
+ * independent queries, all stages on the device.
+ * Per query: EQ (exact queue, size ef) starts with the entry point's exact score.
+ * Each hop reads the best unvisited node u of EQ, marks it visited, ADC-scores the
+ * neighbours of u that have no ADC score yet and pushes them into AQ, then moves the
+ * r = ceil(rerank_ratio * number of those new neighbours) best entries of AQ (fp32
+ * product; AQ holds every ADC-scored node not yet recomputed) to the pending list P.
+ * When |P| >= batch, or EQ has no unvisited node, the chunks in P are re-embedded,
+ * scored by inner product with the query and try-inserted into EQ in P's order
+ * (insert when EQ is not full or the score beats EQ's worst entry, which is evicted).
+ * The search ends when EQ has no unvisited node and P is empty; the k best of EQ
+ * are returned, padded with id -1 / score -inf.
+ * A query's result does not depend on nq or on the other queries of the call:
+ * the encoder batches across queries, never changing a chunk's embedding.
+ *   queries_dev fp32[nq][hidden]; out_ids_dev int64[nq][k]; out_scores_dev fp32[nq][k];
+ *   cache: optional stored embeddings (NULL = none); stats_host: optional totals.
+ * Errors: k < 1, k > ef, ef > 1024, rerank_ratio outside (0,1], batch < 1, entry >= n,
+ * graph/chunk/PQ sizes that disagree -> LEANN_EINVAL / LEANN_ESHAPE; a neighbour id >= n
+ * or a per-query queue overflow -> LEANN_EINVAL / LEANN_ECAPACITY after the run
+ * (outputs then undefined).  Synchronises the stream before returning.
+ */
+int leann_search(leann_ctx *ctx, const float *queries_dev, int64_t nq, const leann_graph *graph,
+                 const leann_pq *pq, const leann_chunks *chunks, const leann_emb_cache *cache, int32_t ef,
+                 int32_t k, float rerank_ratio, int32_t batch, int64_t *out_ids_dev, float *out_scores_dev,
+                 leann_search_stats *stats_host);
+
+/* Tuning knobs (all optional): largest number of tokens one encoder pass holds
+ * (workspace size), and the per-query capacity of the approximate queue. */
+int leann_set_limits(leann_ctx *ctx, int64_t max_tokens_per_pass, int32_t aq_capacity);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LEANN_H */

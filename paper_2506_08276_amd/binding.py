@@ -1,0 +1,222 @@
+"""Thin ctypes binding of libleann.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (include/leann.h).
+Device buffers are torch CUDA tensors (PyTorch is used for device memory and
+the stream, nothing else); the raw data_ptr() values are handed to the library.
+There is no fallback: if the shared library is missing, loading raises.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+import torch  # imported before libleann.so so that both share the HIP runtime torch ships (same soname)
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libleann.so")
+_lib = None
+
+LEANN_F32, LEANN_BF16 = 0, 1
+STATUS = {0: "LEANN_OK", -1: "LEANN_EINVAL", -2: "LEANN_ENOMEM", -3: "LEANN_EDEVICE", -4: "LEANN_ESHAPE",
+          -5: "LEANN_ECAPACITY"}
+EXPORTS = ["leann_last_error", "leann_create", "leann_destroy", "leann_embed", "leann_build_pq", "leann_pq_export",
+           "leann_pq_import", "leann_pq_wrap", "leann_pq_info", "leann_pq_free", "leann_adc", "leann_search",
+           "leann_set_limits"]
+
+
+class LeannError(RuntimeError):
+    def __init__(self, status, message):
+        super().__init__(f"{STATUS.get(status, status)}: {message}")
+        self.status = status
+
+
+class EncoderDesc(C.Structure):
+    _fields_ = [("layers", C.c_int32), ("hidden", C.c_int32), ("heads", C.c_int32), ("ffn", C.c_int32),
+                ("vocab", C.c_int32), ("max_pos", C.c_int32), ("ln_eps", C.c_float)]
+
+
+class Graph(C.Structure):
+    _fields_ = [("row_ptr", C.c_void_p), ("col_idx", C.c_void_p), ("n", C.c_int64), ("entry", C.c_uint32)]
+
+
+class Chunks(C.Structure):
+    _fields_ = [("tokens", C.c_void_p), ("lengths", C.c_void_p), ("n", C.c_int64), ("seq", C.c_int32)]
+
+
+class EmbCache(C.Structure):
+    _fields_ = [("slot_of", C.c_void_p), ("emb", C.c_void_p), ("rows", C.c_int64)]
+
+
+class SearchStats(C.Structure):
+    _fields_ = [("hops", C.c_int64), ("adc_candidates", C.c_int64), ("recomputed_chunks", C.c_int64),
+                ("encoded_chunks", C.c_int64), ("encoded_tokens", C.c_int64), ("flushes", C.c_int64),
+                ("rounds", C.c_int64), ("encoder_ms", C.c_float), ("traverse_ms", C.c_float),
+                ("total_ms", C.c_float)]
+
+    def as_dict(self):
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+def load_library(path=LIB_PATH):
+    """Load libleann.so; raises when it has not been built (no fallback path exists)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(path):
+            raise FileNotFoundError(f"{path} not found: build it with `python -m paper_2506_08276_amd.build` "
+                                    "(or __graft_entry__.build())")
+        lib = C.CDLL(path)
+        lib.leann_last_error.restype = C.c_char_p
+        for name in EXPORTS:
+            getattr(lib, name)
+        lib.leann_destroy.restype = None
+        lib.leann_pq_free.restype = None
+        _lib = lib
+    return _lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise LeannError(rc, load_library().leann_last_error().decode())
+
+
+def _ptr(t):
+    return C.c_void_p(t.data_ptr()) if t is not None else None
+
+
+def _dev(t, dtype, what):
+    assert isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous() and t.dtype == dtype, \
+        f"{what}: need a contiguous CUDA tensor of {dtype}"
+    return t
+
+
+def leann_create(desc, weights, device=0, stream=None):
+    """desc: dict of encoder dimensions; weights: packed CUDA tensor (float32 or bfloat16).  Returns a ctx handle."""
+    lib = load_library()
+    assert weights.is_cuda and weights.is_contiguous() and weights.dtype in (torch.float32, torch.bfloat16)
+    d = EncoderDesc(desc["layers"], desc["hidden"], desc["heads"], desc["ffn"], desc["vocab"], desc["max_pos"],
+                    desc.get("ln_eps", 1e-12))
+    ctx = C.c_void_p()
+    if stream is None:
+        stream = torch.cuda.current_stream(device).cuda_stream
+    _check(lib.leann_create(C.byref(ctx), C.byref(d), _ptr(weights),
+                            LEANN_F32 if weights.dtype == torch.float32 else LEANN_BF16, C.c_int(device),
+                            C.c_void_p(stream)))
+    return ctx
+
+
+def leann_destroy(ctx):
+    load_library().leann_destroy(ctx)
+
+
+def leann_set_limits(ctx, max_tokens_per_pass=0, aq_capacity=0):
+    _check(load_library().leann_set_limits(ctx, C.c_int64(max_tokens_per_pass), C.c_int32(aq_capacity)))
+
+
+def _chunks(tokens, lengths):
+    _dev(tokens, torch.int32, "tokens")
+    _dev(lengths, torch.int32, "lengths")
+    assert tokens.dim() == 2 and lengths.numel() == tokens.shape[0]
+    return Chunks(tokens.data_ptr(), lengths.data_ptr(), tokens.shape[0], tokens.shape[1])
+
+
+def leann_embed(ctx, tokens, lengths, ids=None, n_ids=None, hidden=None, out=None):
+    """Embeddings fp32 [n_ids][hidden] of chunks `ids` (int64 CUDA tensor) or of the first n_ids chunks."""
+    lib = load_library()
+    ch = _chunks(tokens, lengths)
+    if ids is not None:
+        _dev(ids, torch.int64, "ids")
+        n_ids = ids.numel()
+    elif n_ids is None:
+        n_ids = tokens.shape[0]
+    if out is None:
+        out = torch.empty((n_ids, hidden), dtype=torch.float32, device=tokens.device)
+    _dev(out, torch.float32, "out")
+    _check(lib.leann_embed(ctx, C.byref(ch), _ptr(ids), C.c_int64(n_ids), _ptr(out)))
+    return out
+
+
+def leann_build_pq(ctx, emb, m_sub, iters, seed):
+    _dev(emb, torch.float32, "emb")
+    pq = C.c_void_p()
+    _check(load_library().leann_build_pq(ctx, _ptr(emb), C.c_int64(emb.shape[0]), C.c_int32(emb.shape[1]),
+                                         C.c_int32(m_sub), C.c_int32(iters), C.c_uint64(seed), C.byref(pq)))
+    return pq
+
+
+def leann_pq_info(pq):
+    n, d, m = C.c_int64(), C.c_int32(), C.c_int32()
+    _check(load_library().leann_pq_info(pq, C.byref(n), C.byref(d), C.byref(m)))
+    return n.value, d.value, m.value
+
+
+def leann_pq_export(ctx, pq):
+    """Returns (codebook float32 [m_sub][256][dsub], codes uint8 [n][m_sub]) as numpy arrays."""
+    n, d, m = leann_pq_info(pq)
+    cb = np.empty((m, 256, d // m), dtype=np.float32)
+    codes = np.empty((n, m), dtype=np.uint8)
+    _check(load_library().leann_pq_export(ctx, pq, cb.ctypes.data_as(C.c_void_p), codes.ctypes.data_as(C.c_void_p)))
+    return cb, codes
+
+
+def leann_pq_import(ctx, codebook, codes):
+    codebook = np.ascontiguousarray(codebook, dtype=np.float32)
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    m, ksub, dsub = codebook.shape
+    assert ksub == 256 and codes.shape[1] == m
+    pq = C.c_void_p()
+    _check(load_library().leann_pq_import(ctx, codebook.ctypes.data_as(C.c_void_p), codes.ctypes.data_as(C.c_void_p),
+                                          C.c_int64(codes.shape[0]), C.c_int32(m * dsub), C.c_int32(m), C.byref(pq)))
+    return pq
+
+
+def leann_pq_wrap(ctx, codebook, codes_dev):
+    codebook = np.ascontiguousarray(codebook, dtype=np.float32)
+    _dev(codes_dev, torch.uint8, "codes")
+    m, ksub, dsub = codebook.shape
+    assert ksub == 256 and codes_dev.shape[1] == m
+    pq = C.c_void_p()
+    _check(load_library().leann_pq_wrap(ctx, codebook.ctypes.data_as(C.c_void_p), _ptr(codes_dev),
+                                        C.c_int64(codes_dev.shape[0]), C.c_int32(m * dsub), C.c_int32(m),
+                                        C.byref(pq)))
+    return pq
+
+
+def leann_pq_free(pq):
+    load_library().leann_pq_free(pq)
+
+
+def leann_adc(ctx, queries, pq, cand_ids, out=None):
+    """ADC similarities fp32 [nq][nc] of candidate node ids (uint32 stored in an int32 CUDA tensor)."""
+    _dev(queries, torch.float32, "queries")
+    _dev(cand_ids, torch.int32, "cand_ids")
+    nq, nc = cand_ids.shape
+    if out is None:
+        out = torch.empty((nq, nc), dtype=torch.float32, device=queries.device)
+    _check(load_library().leann_adc(ctx, _ptr(queries), C.c_int64(nq), pq, _ptr(cand_ids), C.c_int32(nc), _ptr(out)))
+    return out
+
+
+def leann_search(ctx, queries, graph, pq, tokens, lengths, ef, k, rerank_ratio, batch, cache=None):
+    """graph = (row_ptr int64 CUDA tensor holding uint64 values, col_idx int32 CUDA tensor holding uint32, entry).
+    cache = (slot_of int32 [n], emb float32 [rows][d]) or None.
+    Returns (ids int64 [nq][k], scores float32 [nq][k], stats dict)."""
+    _dev(queries, torch.float32, "queries")
+    row_ptr, col_idx, entry = graph
+    _dev(row_ptr, torch.int64, "row_ptr")
+    _dev(col_idx, torch.int32, "col_idx")
+    g = Graph(row_ptr.data_ptr(), col_idx.data_ptr(), row_ptr.numel() - 1, int(entry))
+    ch = _chunks(tokens, lengths)
+    nq = queries.shape[0]
+    ids = torch.empty((nq, k), dtype=torch.int64, device=queries.device)
+    scores = torch.empty((nq, k), dtype=torch.float32, device=queries.device)
+    st = SearchStats()
+    cref = None
+    if cache is not None:
+        slot_of, emb = cache
+        _dev(slot_of, torch.int32, "slot_of")
+        _dev(emb, torch.float32, "cache emb")
+        cstruct = EmbCache(slot_of.data_ptr(), emb.data_ptr(), emb.shape[0])
+        cref = C.byref(cstruct)
+    _check(load_library().leann_search(ctx, _ptr(queries), C.c_int64(nq), C.byref(g), pq, C.byref(ch), cref,
+                                       C.c_int32(ef), C.c_int32(k), C.c_float(rerank_ratio), C.c_int32(batch),
+                                       _ptr(ids), _ptr(scores), C.byref(st)))
+    return ids, scores, st.as_dict()

@@ -1,0 +1,525 @@
+// Encoder forward pass for embedding recomputation (LEANN Alg. 2 "Recompute embedding x_c"; Sec. 3 online
+// stage), written for gfx950: bf16 MFMA GEMMs with LDS-staged, swizzled tiles, an MFMA attention kernel
+// working on ragged (token-packed) batches, and fp32 LayerNorm / pooling.
+//
+// Tokens of all chunks of a pass are packed back to back (no padding rows): chunk i owns rows
+// cu[i] .. cu[i+1] of every activation matrix.  The number of valid rows T is only known on the device,
+// so grids are sized for the worst case and blocks beyond T leave at once.
+#include "common.h"
+
+namespace {
+
+__device__ inline float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+
+// ------------------------------------------------------------------ pass set-up
+// lengths of the requested chunks -> exclusive prefix sum cu[0..n], cu[n] = T.  One block of 1024 threads.
+__global__ __launch_bounds__(1024) void prep_kernel(const int32_t *__restrict__ lengths, const int64_t *__restrict__ ids,
+                                                    int64_t first_id, int n, int64_t n_store, int seq,
+                                                    int32_t *__restrict__ cu, int64_t *__restrict__ chunk_of,
+                                                    int *__restrict__ err, int64_t *__restrict__ tok_count)
+{
+    __shared__ int part[1024];
+    const int tid = threadIdx.x;
+    const int per = (n + 1023) / 1024;
+    const int beg = tid * per, end = min(n, beg + per);
+    int s = 0;
+    for (int i = beg; i < end; ++i) {
+        int64_t id = ids ? ids[i] : first_id + i;
+        int len = 0;
+        if (id < 0 || id >= n_store) {
+            atomicOr(err, 1);
+            id = 0;
+        } else {
+            len = lengths[id];
+            if (len < 1 || len > seq) {
+                atomicOr(err, 2);
+                len = 0;
+            }
+        }
+        chunk_of[i] = id;
+        cu[i] = len;  // temporarily the length
+        s += len;
+    }
+    part[tid] = s;
+    __syncthreads();
+    for (int o = 1; o < 1024; o <<= 1) {
+        int v = tid >= o ? part[tid - o] : 0;
+        __syncthreads();
+        part[tid] += v;
+        __syncthreads();
+    }
+    int run = tid ? part[tid - 1] : 0;
+    for (int i = beg; i < end; ++i) {
+        int len = cu[i];
+        cu[i] = run;
+        run += len;
+    }
+    if (tid == 1023) {
+        cu[n] = part[1023];
+        if (tok_count) *tok_count += part[1023];
+    }
+}
+
+// ------------------------------------------------------------------ embedding + LayerNorm
+// one wave per (chunk, position); x[cu[i]+t] = LN(tok_emb[id] + pos_emb[t] + seg_emb) in bf16
+__global__ __launch_bounds__(256) void embed_ln_kernel(const int32_t *__restrict__ tokens, const int64_t *__restrict__ chunk_of,
+                                                       const int32_t *__restrict__ cu, int n, int seq, int d, int vocab,
+                                                       const bf16_t *__restrict__ tok_emb, const bf16_t *__restrict__ pos_emb,
+                                                       const bf16_t *__restrict__ seg_emb, const float *__restrict__ g,
+                                                       const float *__restrict__ b, float eps, bf16_t *__restrict__ x,
+                                                       int *__restrict__ err)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t w = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int i = (int)(w / seq), t = (int)(w % seq);
+    if (i >= n) return;
+    const int row0 = cu[i], len = cu[i + 1] - row0;
+    if (t >= len) return;
+    int tok = tokens[chunk_of[i] * seq + t];
+    if (tok < 0 || tok >= vocab) {
+        if (lane == 0) atomicOr(err, 4);
+        tok = 0;
+    }
+    const int per = d >> 6;
+    float v[16];
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < 16; ++j)
+        if (j < per) {
+            int c = j * 64 + lane;
+            v[j] = (float)tok_emb[(size_t)tok * d + c] + (float)pos_emb[(size_t)t * d + c] + (float)seg_emb[c];
+            s += v[j];
+        }
+    const float mean = wave_sum(s) / (float)d;
+    float q = 0.f;
+#pragma unroll
+    for (int j = 0; j < 16; ++j)
+        if (j < per) {
+            float c = v[j] - mean;
+            q += c * c;
+        }
+    const float inv = 1.0f / sqrtf(wave_sum(q) / (float)d + eps);
+    bf16_t *xr = x + (size_t)(row0 + t) * d;
+#pragma unroll
+    for (int j = 0; j < 16; ++j)
+        if (j < per) {
+            int c = j * 64 + lane;
+            xr[c] = (bf16_t)((v[j] - mean) * inv * g[c] + b[c]);
+        }
+}
+
+// ------------------------------------------------------------------ LayerNorm of fp32 rows -> bf16
+__global__ __launch_bounds__(256) void ln_kernel(const float *__restrict__ in, const float *__restrict__ g,
+                                                 const float *__restrict__ b, bf16_t *__restrict__ out,
+                                                 const int32_t *__restrict__ T_dev, int d, float eps)
+{
+    const int lane = threadIdx.x & 63;
+    const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= *T_dev) return;
+    const int per = d >> 6;
+    const float *ir = in + (size_t)row * d;
+    float v[16];
+    float s = 0.f;
+#pragma unroll
+    for (int j = 0; j < 16; ++j)
+        if (j < per) {
+            v[j] = ir[j * 64 + lane];
+            s += v[j];
+        }
+    const float mean = wave_sum(s) / (float)d;
+    float q = 0.f;
+#pragma unroll
+    for (int j = 0; j < 16; ++j)
+        if (j < per) {
+            float c = v[j] - mean;
+            q += c * c;
+        }
+    const float inv = 1.0f / sqrtf(wave_sum(q) / (float)d + eps);
+    bf16_t *orow = out + (size_t)row * d;
+#pragma unroll
+    for (int j = 0; j < 16; ++j)
+        if (j < per) {
+            int c = j * 64 + lane;
+            orow[c] = (bf16_t)((v[j] - mean) * inv * g[c] + b[c]);
+        }
+}
+
+// ------------------------------------------------------------------ GEMM
+// C[T][N] = A[T][K] * W[N][K]^T (+ epilogue).  bf16 operands, fp32 accumulation in MFMA 32x32x16.
+// Block tile BM x BN x 64, four waves in a 2x2 grid, two LDS stages.  A 64-element K-slab of a row is
+// eight 16-byte chunks; chunk c of row r lives at chunk position c ^ ((r >> 1) & 7) so that both the
+// row-wise stores and the column-of-rows MFMA operand reads spread over all banks.
+// Each output element is one fixed-order sum over K: a row's result does not depend on T.
+enum { EPI_BIAS = 0, EPI_BIAS_GELU = 1, EPI_BIAS_RES_F32 = 2 };
+
+__device__ inline float gelu_erf(float v) { return 0.5f * v * (1.0f + erff(v * 0.70710678118654752440f)); }
+
+template <int BM, int BN, int EPI>
+__global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W,
+                                                   const float *__restrict__ bias, const bf16_t *__restrict__ res,
+                                                   void *__restrict__ out, const int32_t *__restrict__ T_dev, int N, int K,
+                                                   int tiles_n)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    bf16_t *As = reinterpret_cast<bf16_t *>(smem);
+    bf16_t *Bs = As + 2 * BM * 64;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    constexpr int TM = BM / 64, TN = BN / 64;
+
+    // Blocks go round-robin to the 8 XCDs; give each XCD a contiguous run of tiles (same A rows, all
+    // column tiles) so that the A slab is reused out of that XCD's L2.
+    const int T = *T_dev;
+    const int n_tiles = ((T + BM - 1) / BM) * tiles_n;
+    const int nb = (n_tiles + 7) & ~7;
+    if ((int)blockIdx.x >= nb) return;
+    const int logical = (blockIdx.x & 7) * (nb >> 3) + (blockIdx.x >> 3);
+    if (logical >= n_tiles) return;
+    const int tile_m = logical / tiles_n, tile_n = logical % tiles_n;
+
+    const bf16_t *Ag = A + (size_t)tile_m * BM * K;
+    const bf16_t *Wg = W + (size_t)tile_n * BN * K;
+    constexpr int ACH = BM * 8 / 256, BCH = BN * 8 / 256;
+    uint4 ra[ACH], rb[BCH];
+
+    auto gload = [&](int k0) {
+#pragma unroll
+        for (int i = 0; i < ACH; ++i) {
+            int ci = tid + 256 * i, row = ci >> 3, c = ci & 7;
+            ra[i] = *reinterpret_cast<const uint4 *>(Ag + (size_t)row * K + k0 + c * 8);
+        }
+#pragma unroll
+        for (int i = 0; i < BCH; ++i) {
+            int ci = tid + 256 * i, row = ci >> 3, c = ci & 7;
+            rb[i] = *reinterpret_cast<const uint4 *>(Wg + (size_t)row * K + k0 + c * 8);
+        }
+    };
+    auto sstore = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < ACH; ++i) {
+            int ci = tid + 256 * i, row = ci >> 3, c = ci & 7;
+            *reinterpret_cast<uint4 *>(As + buf * BM * 64 + row * 64 + ((c ^ ((row >> 1) & 7)) << 3)) = ra[i];
+        }
+#pragma unroll
+        for (int i = 0; i < BCH; ++i) {
+            int ci = tid + 256 * i, row = ci >> 3, c = ci & 7;
+            *reinterpret_cast<uint4 *>(Bs + buf * BN * 64 + row * 64 + ((c ^ ((row >> 1) & 7)) << 3)) = rb[i];
+        }
+    };
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+
+    const int KT = K >> 6;
+    gload(0);
+    sstore(0);
+    __syncthreads();
+    for (int kt = 0; kt < KT; ++kt) {
+        if (kt + 1 < KT) gload((kt + 1) << 6);
+        const bf16_t *as = As + (kt & 1) * BM * 64;
+        const bf16_t *bs = Bs + (kt & 1) * BN * 64;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            bf16x8 af[TM], bfr[TN];
+            const int c = ks * 2 + (lane >> 5);
+#pragma unroll
+            for (int mi = 0; mi < TM; ++mi) {
+                int row = wm * (BM / 2) + mi * 32 + (lane & 31);
+                af[mi] = *reinterpret_cast<const bf16x8 *>(as + row * 64 + ((c ^ ((row >> 1) & 7)) << 3));
+            }
+#pragma unroll
+            for (int ni = 0; ni < TN; ++ni) {
+                int row = wn * (BN / 2) + ni * 32 + (lane & 31);
+                bfr[ni] = *reinterpret_cast<const bf16x8 *>(bs + row * 64 + ((c ^ ((row >> 1) & 7)) << 3));
+            }
+#pragma unroll
+            for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+                for (int ni = 0; ni < TN; ++ni)
+                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[ni], acc[mi][ni], 0, 0, 0);
+        }
+        if (kt + 1 < KT) sstore((kt + 1) & 1);
+        __syncthreads();
+    }
+
+    // accumulator register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32 of its 32x32 tile
+#pragma unroll
+    for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < TN; ++ni) {
+            const int col = tile_n * BN + wn * (BN / 2) + ni * 32 + (lane & 31);
+            const float bv = bias[col];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row = tile_m * BM + wm * (BM / 2) + mi * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                const size_t o = (size_t)row * N + col;
+                float v = acc[mi][ni][r] + bv;
+                if (EPI == EPI_BIAS) {
+                    reinterpret_cast<bf16_t *>(out)[o] = (bf16_t)v;
+                } else if (EPI == EPI_BIAS_GELU) {
+                    reinterpret_cast<bf16_t *>(out)[o] = (bf16_t)gelu_erf(v);
+                } else {
+                    reinterpret_cast<float *>(out)[o] = v + (float)res[o];
+                }
+            }
+        }
+}
+
+// ------------------------------------------------------------------ attention
+// One block per (chunk, head), head size 64, up to 256 keys.  K (row-major, swizzled) and V^T live in LDS.
+// Each wave takes 32 query rows at a time and computes S^T = K Q^T with MFMA, so that a lane owns one
+// query column: the softmax reductions run over the lane's own registers plus one exchange with lane^32.
+// P^T (bf16) then feeds O^T = V^T P^T directly from registers: accumulator registers 8u..8u+7 of key tile t
+// are exactly the eight k-slots of one MFMA step when V^T is read with the matching key order.
+constexpr int ATT_VS = 256 + 4;  // V^T row stride (bf16 elements)
+constexpr int ATT_SMEM = (256 * 64 + 64 * ATT_VS) * (int)sizeof(bf16_t);
+
+__global__ __launch_bounds__(256) void attention_kernel(const bf16_t *__restrict__ qkv, const int32_t *__restrict__ cu,
+                                                        bf16_t *__restrict__ out, int d, float scale_log2e)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    bf16_t *Ks = reinterpret_cast<bf16_t *>(smem);  // [256][64]
+    bf16_t *Vt = Ks + 256 * 64;                     // [64][ATT_VS]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c = blockIdx.x, h = blockIdx.y;
+    const int t0 = cu[c], L = cu[c + 1] - t0;
+    if (L <= 0) return;
+    const int nkt = (L + 31) >> 5;
+    const int Lp = nkt << 5;
+    const size_t ld = (size_t)3 * d;
+    const bf16_t *kbase = qkv + (size_t)t0 * ld + d + h * 64;
+    const bf16_t *vbase = qkv + (size_t)t0 * ld + 2 * d + h * 64;
+
+    for (int idx = tid; idx < Lp * 8; idx += 256) {
+        const int key = idx >> 3, ch = idx & 7;
+        uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
+        if (key < L) {
+            kv = *reinterpret_cast<const uint4 *>(kbase + (size_t)key * ld + ch * 8);
+            vv = *reinterpret_cast<const uint4 *>(vbase + (size_t)key * ld + ch * 8);
+        }
+        *reinterpret_cast<uint4 *>(Ks + key * 64 + ((ch ^ ((key >> 1) & 7)) << 3)) = kv;
+        const bf16_t *ve = reinterpret_cast<const bf16_t *>(&vv);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) Vt[(ch * 8 + i) * ATT_VS + key] = ve[i];
+    }
+    __syncthreads();
+
+    const int half = lane >> 5, l32 = lane & 31;
+    for (int qb = wave; qb < nkt; qb += 4) {
+        const int qrow = qb * 32 + l32;
+        const int qload = min(qrow, L - 1);
+        const bf16_t *qp = qkv + (size_t)(t0 + qload) * ld + h * 64;
+        bf16x8 qf[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) qf[s] = *reinterpret_cast<const bf16x8 *>(qp + s * 16 + half * 8);
+
+        f32x16 sc[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sc[t][r] = 0.f;
+            if (t < nkt) {
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    const int row = t * 32 + l32, ch = s * 2 + half;
+                    bf16x8 kf = *reinterpret_cast<const bf16x8 *>(Ks + row * 64 + ((ch ^ ((row >> 1) & 7)) << 3));
+                    sc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[s], sc[t], 0, 0, 0);
+                }
+            }
+        }
+        // lane owns query column l32 and keys 32t + 8(r/4) + 4*half + r%4
+        float mx = -INFINITY;
+#pragma unroll
+        for (int t = 0; t < 8; ++t)
+            if (t < nkt) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int key = t * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
+                    if (key >= L) sc[t][r] = -INFINITY;
+                    mx = fmaxf(mx, sc[t][r]);
+                }
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float moff = mx * scale_log2e;
+        float den = 0.f;
+#pragma unroll
+        for (int t = 0; t < 8; ++t)
+            if (t < nkt) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    float p = exp2f(sc[t][r] * scale_log2e - moff);
+                    sc[t][r] = p;
+                    den += p;
+                }
+            }
+        den += __shfl_xor(den, 32, 64);
+
+        f32x16 oacc[2];
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
+#pragma unroll
+        for (int t = 0; t < 8; ++t)
+            if (t < nkt) {
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    bf16x8 pf;
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) pf[i] = (bf16_t)sc[t][8 * u + i];
+                    const int k0 = t * 32 + u * 16 + 4 * half;  // slots 0..3 -> keys k0..k0+3, slots 4..7 -> k0+8..k0+11
+#pragma unroll
+                    for (int dt = 0; dt < 2; ++dt) {
+                        const bf16_t *vr = Vt + (dt * 32 + l32) * ATT_VS + k0;
+                        bf16x4 lo = *reinterpret_cast<const bf16x4 *>(vr);
+                        bf16x4 hi = *reinterpret_cast<const bf16x4 *>(vr + 8);
+                        bf16x8 vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                        oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[dt], 0, 0, 0);
+                    }
+                }
+            }
+        if (qrow < L) {
+            const float inv = 1.0f / den;
+            bf16_t *op = out + (size_t)(t0 + qrow) * d + h * 64;
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    bf16x4 o4;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) o4[i] = (bf16_t)(oacc[dt][4 * g + i] * inv);
+                    *reinterpret_cast<bf16x4 *>(op + dt * 32 + 8 * g + 4 * half) = o4;
+                }
+        }
+    }
+}
+
+// ------------------------------------------------------------------ masked mean pool + L2 normalise
+__global__ __launch_bounds__(256) void pool_kernel(const bf16_t *__restrict__ x, const int32_t *__restrict__ cu, int d,
+                                                   float *__restrict__ out)
+{
+    __shared__ float red[256];
+    const int c = blockIdx.x, tid = threadIdx.x;
+    const int t0 = cu[c], L = cu[c + 1] - t0;
+    float v[4] = {0.f, 0.f, 0.f, 0.f};
+    float sq = 0.f;
+    if (L > 0) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int col = tid + 256 * j;
+            if (col < d) {
+                float s = 0.f;
+                for (int t = 0; t < L; ++t) s += (float)x[(size_t)(t0 + t) * d + col];
+                v[j] = s / (float)L;
+                sq += v[j] * v[j];
+            }
+        }
+    }
+    red[tid] = sq;
+    __syncthreads();
+    for (int o = 128; o > 0; o >>= 1) {
+        if (tid < o) red[tid] += red[tid + o];
+        __syncthreads();
+    }
+    const float nrm = fmaxf(sqrtf(red[0]), 1e-12f);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int col = tid + 256 * j;
+        if (col < d) out[(size_t)c * d + col] = v[j] / nrm;
+    }
+}
+
+template <int BM, int BN, int EPI>
+int launch_gemm(leann_ctx *ctx, const bf16_t *A, const bf16_t *W, const float *bias, const bf16_t *res, void *out,
+                const int32_t *T_dev, int max_rows, int N, int K)
+{
+    static bool attr_done = false;
+    constexpr int smem = 2 * (BM + BN) * 64 * (int)sizeof(bf16_t);
+    if (!attr_done) {
+        LEANN_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_kernel<BM, BN, EPI>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, smem));
+        attr_done = true;
+    }
+    const int tiles_n = N / BN;
+    const int tiles = ((max_rows + BM - 1) / BM) * tiles_n;
+    const int grid = (tiles + 7) & ~7;
+    hipLaunchKernelGGL((gemm_kernel<BM, BN, EPI>), dim3(grid), dim3(256), smem, ctx->stream, A, W, bias, res, out, T_dev,
+                       N, K, tiles_n);
+    LEANN_HIP(hipGetLastError());
+    return LEANN_OK;
+}
+
+}  // namespace
+
+int enc_forward(leann_ctx *ctx, const leann_chunks *chunks, const int64_t *ids_dev, int64_t first_id, int64_t n,
+                float *out_dev, int *err_dev, int64_t *tok_count_dev)
+{
+    const leann_encoder_desc &e = ctx->desc;
+    const int d = e.hidden, F = e.ffn, H = e.heads, seq = chunks->seq;
+    if (n <= 0) return LEANN_OK;
+    if (seq < 1 || seq > 256 || seq > e.max_pos) {
+        leann_set_error("sequence length %d not covered (1..min(256, max_pos))", seq);
+        return LEANN_ESHAPE;
+    }
+    int64_t per_pass = ctx->max_tokens / seq;
+    if (per_pass < 1) per_pass = 1;
+    if (per_pass > n) per_pass = n;
+    const size_t rows = (size_t)per_pass * seq + 256;
+    LEANN_TRY(ctx->x.reserve(rows * d * sizeof(bf16_t)));
+    LEANN_TRY(ctx->qkv.reserve(rows * 3 * d * sizeof(bf16_t)));
+    LEANN_TRY(ctx->att.reserve(rows * d * sizeof(bf16_t)));
+    LEANN_TRY(ctx->pre.reserve(rows * d * sizeof(float)));
+    LEANN_TRY(ctx->hid.reserve(rows * F * sizeof(bf16_t)));
+    LEANN_TRY(ctx->cu.reserve((size_t)(per_pass + 1) * sizeof(int32_t)));
+    LEANN_TRY(ctx->enc_ids.reserve((size_t)per_pass * sizeof(int64_t)));
+    bf16_t *x = (bf16_t *)ctx->x.p, *qkv = (bf16_t *)ctx->qkv.p, *att = (bf16_t *)ctx->att.p, *hid = (bf16_t *)ctx->hid.p;
+    float *pre = (float *)ctx->pre.p;
+    int32_t *cu = (int32_t *)ctx->cu.p;
+    int64_t *chunk_of = (int64_t *)ctx->enc_ids.p;
+    const float scale_log2e = 1.4426950408889634f / sqrtf((float)(d / H));
+    static bool att_attr = false;
+    if (!att_attr) {
+        LEANN_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(attention_kernel),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, ATT_SMEM));
+        att_attr = true;
+    }
+
+    for (int64_t s = 0; s < n; s += per_pass) {
+        const int m = (int)((n - s < per_pass) ? n - s : per_pass);
+        const int max_rows = m * seq;
+        const int32_t *T_dev = cu + m;
+        hipLaunchKernelGGL(prep_kernel, dim3(1), dim3(1024), 0, ctx->stream, chunks->lengths,
+                           ids_dev ? ids_dev + s : nullptr, first_id + s, m, chunks->n, seq, cu, chunk_of, err_dev,
+                           tok_count_dev);
+        hipLaunchKernelGGL(embed_ln_kernel, dim3((unsigned)(((int64_t)m * seq + 3) / 4)), dim3(256), 0, ctx->stream,
+                           chunks->tokens, chunk_of, cu, m, seq, d, e.vocab, ctx->tok_emb, ctx->pos_emb, ctx->seg_emb,
+                           ctx->emb_g, ctx->emb_b, e.ln_eps, x, err_dev);
+        const int ln_grid = (max_rows + 3) / 4;
+        for (int l = 0; l < e.layers; ++l) {
+            const LayerWeights &w = ctx->layers[l];
+            LEANN_TRY((launch_gemm<128, 128, EPI_BIAS>(ctx, x, w.wqkv, w.bqkv, nullptr, qkv, T_dev, max_rows, 3 * d, d)));
+            hipLaunchKernelGGL(attention_kernel, dim3(m, H), dim3(256), ATT_SMEM, ctx->stream, qkv, cu, att, d,
+                               scale_log2e);
+            LEANN_TRY((launch_gemm<128, 128, EPI_BIAS_RES_F32>(ctx, att, w.wo, w.bo, x, pre, T_dev, max_rows, d, d)));
+            hipLaunchKernelGGL(ln_kernel, dim3(ln_grid), dim3(256), 0, ctx->stream, pre, w.g1, w.be1, x, T_dev, d,
+                               e.ln_eps);
+            LEANN_TRY((launch_gemm<128, 128, EPI_BIAS_GELU>(ctx, x, w.w1, w.b1, nullptr, hid, T_dev, max_rows, F, d)));
+            LEANN_TRY((launch_gemm<128, 128, EPI_BIAS_RES_F32>(ctx, hid, w.w2, w.b2, x, pre, T_dev, max_rows, d, F)));
+            hipLaunchKernelGGL(ln_kernel, dim3(ln_grid), dim3(256), 0, ctx->stream, pre, w.g2, w.be2, x, T_dev, d,
+                               e.ln_eps);
+        }
+        hipLaunchKernelGGL(pool_kernel, dim3(m), dim3(256), 0, ctx->stream, x, cu, d, out_dev + (size_t)s * d);
+        LEANN_HIP(hipGetLastError());
+    }
+    return LEANN_OK;
+}

@@ -1,0 +1,209 @@
+"""GPU parity: leann_search against the search oracle on config 1 ("Tiny") and on edge cases.
+
+Two layers of comparison:
+  (a) search logic alone -- the GPU is given the oracle's fp32 embeddings through the stored-embedding table
+      (cache covering every node), so both sides see identical exact scores up to summation order: ids,
+      per-query scores and the hop / ADC / recompute / flush counts must agree exactly;
+  (b) the full path with on-device recomputation (bf16 encoder): top-k ids must agree with the oracle wherever
+      the oracle's score gaps exceed 1e-3 (the benchmark spec), reported with the gap statistics.
+"""
+import numpy as np
+import pytest
+
+import leann_inputs as li
+from gpu_util import say, tiny_world, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def L():
+    import paper_2506_08276_amd as L
+    L.load_library()
+    return L
+
+
+@pytest.fixture(scope="module")
+def world(L, orc):
+    w = tiny_world(orc)
+    ctx = L.leann_create(w["cfg"], to_dev(w["w"]))
+    w["ctx"] = ctx
+    w["pq"] = L.leann_pq_import(ctx, w["cb"], w["codes"])
+    w["graph"] = (to_dev(w["row_ptr"]), to_dev(w["col_idx"]), w["entry"])
+    w["t"], w["l"] = to_dev(w["tokens"]), to_dev(w["lengths"])
+    w["q"] = to_dev(w["queries"])
+    w["full_cache"] = (to_dev(np.arange(w["n"], dtype=np.int32)), to_dev(w["emb"]))
+    w["emb_bf16"] = orc.embed(w["desc"], w["w"], w["tokens"], w["lengths"], precision=1)
+    yield w
+    L.leann_pq_free(w["pq"])
+    L.leann_destroy(ctx)
+
+
+def oracle_runs(orc, w, queries, table, ef, k, alpha, batch):
+    return [orc.search_table(q, w["row_ptr"], w["col_idx"], w["entry"], w["cb"], w["codes"], table, ef, k, alpha, batch)
+            for q in queries]
+
+
+@pytest.mark.parametrize("ef,k,alpha,batch", [(32, 3, 0.2, 32), (32, 3, 0.2, 1), (16, 5, 1.0, 1), (64, 3, 0.05, 7),
+                                             (8, 8, 0.5, 100000), (200, 10, 0.3, 64)])
+def test_search_logic_exact_with_stored_embeddings(L, orc, world, ef, k, alpha, batch):
+    w = world
+    say(f"search logic ef={ef} k={k} alpha={alpha} batch={batch}")
+    ids, scores, st = L.leann_search(w["ctx"], w["q"], w["graph"], w["pq"], w["t"], w["l"], ef, k, alpha, batch,
+                                     cache=w["full_cache"])
+    ids, scores = ids.cpu().numpy(), scores.cpu().numpy()
+    runs = oracle_runs(orc, w, w["queries"], w["emb"], ef, k, alpha, batch)
+    for qi, r in enumerate(runs):
+        assert list(ids[qi]) == list(r["ids"]), (qi, ids[qi], r["ids"])
+        np.testing.assert_allclose(scores[qi], r["scores"], atol=2e-6)
+    for key, okey in (("hops", "hops"), ("adc_candidates", "adc_candidates"), ("recomputed_chunks", "recomputed"),
+                      ("flushes", "flushes")):
+        assert st[key] == sum(r["stats"][okey] for r in runs), key
+    assert st["encoded_chunks"] == 0  # everything came from the stored table
+
+
+def test_result_independent_of_concurrency(L, world):
+    import torch
+    w = world
+    say("one query at a time vs all together (recomputing path)")
+    ids_all, sc_all, _ = L.leann_search(w["ctx"], w["q"], w["graph"], w["pq"], w["t"], w["l"], 32, 3, 0.2, 32)
+    for qi in (0, 7, 15):
+        ids1, sc1, _ = L.leann_search(w["ctx"], w["q"][qi:qi + 1].contiguous(), w["graph"], w["pq"], w["t"], w["l"],
+                                      32, 3, 0.2, 32)
+        assert torch.equal(ids1[0], ids_all[qi]) and torch.equal(sc1[0], sc_all[qi])
+    ids_again, sc_again, _ = L.leann_search(w["ctx"], w["q"], w["graph"], w["pq"], w["t"], w["l"], 32, 3, 0.2, 32)
+    assert torch.equal(ids_again, ids_all) and torch.equal(sc_again, sc_all)
+
+
+def decided_ranks(log_scores, k, gap=1e-3):
+    """Ranks (0-based) of the oracle's top-k whose score is more than `gap` away from both neighbours in the
+    oracle's sorted list of exact scores: there the id is decided by more than the precision difference."""
+    ls = np.sort(log_scores)[::-1]
+    ls = np.concatenate([ls, np.full(k + 1, -np.inf)])
+    return [j for j in range(k) if (j == 0 or ls[j - 1] - ls[j] > gap) and ls[j] - ls[j + 1] > gap]
+
+
+def full_path_case(L, orc, w, ctx, pq, graph, t, l, q, ef, k, alpha, batch, label):
+    say(f"{label}: full path ef={ef} k={k} alpha={alpha} batch={batch}")
+    ids, scores, st = L.leann_search(ctx, q, graph, pq, t, l, ef, k, alpha, batch)
+    ids, scores = ids.cpu().numpy(), scores.cpu().numpy()
+    runs = oracle_runs(orc, w, w["queries"], w["emb"], ef, k, alpha, batch)
+    # second oracle run in the kernel's storage precision: a rank is compared only if this change of precision
+    # does not move the oracle's own answer (the search is a heuristic whose trajectory can fork at a near-tie
+    # anywhere along the way, not only at the output)
+    runs_bf = oracle_runs(orc, w, w["queries"], w["emb_bf16"], ef, k, alpha, batch)
+    gpu_emb = L.leann_embed(ctx, t, l, hidden=w["cfg"]["hidden"]).cpu().numpy()
+    assert np.abs(gpu_emb - w["emb"]).max() <= 2e-2
+    decided = agree = full = 0
+    for qi, r in enumerate(runs):
+        # the returned exact scores are <q, e_c> of the embeddings leann_embed gives for the same chunks
+        np.testing.assert_allclose(scores[qi], gpu_emb[ids[qi]] @ w["queries"][qi], atol=1e-5)
+        assert len(set(ids[qi])) == k
+        ranks = [j for j in decided_ranks(r["log_scores"], k) if runs_bf[qi]["ids"][j] == r["ids"][j]]
+        decided += len(ranks)
+        for j in ranks:
+            assert ids[qi][j] == r["ids"][j], (label, qi, j, ids[qi], r["ids"], np.sort(r["log_scores"])[::-1][:k + 1])
+        agree += sum(int(a == b) for a, b in zip(ids[qi], r["ids"]))
+        full += list(ids[qi]) == list(r["ids"])
+    nq = len(runs)
+    print(f"{label}: {decided}/{nq * k} ranks decided (gap > 1e-3, stable under bf16 storage) and all equal; {agree}/{nq * k} ranks and "
+          f"{full}/{nq} whole results equal to the fp32 oracle's; stats {st}")
+    assert st["recomputed_chunks"] > 0 and st["encoded_chunks"] == st["recomputed_chunks"]
+    return decided
+
+
+def test_config1_full_path_against_oracle(L, orc, world):
+    """Config 1 with on-device recomputation (bf16 encoder): ids agree with the fp32 oracle at every rank the
+    oracle's score gaps (> 1e-3 on both sides) decide.  Random-init embeddings of uniform tokens are nearly
+    collinear, so few ranks are decided here; the topic-structured variant below has many."""
+    w = world
+    full_path_case(L, orc, w, w["ctx"], w["pq"], w["graph"], w["t"], w["l"], w["q"], 32, 3, 0.2, 32, "config 1")
+
+
+def test_structured_tiny_full_path_against_oracle(L, orc):
+    """Same shapes as config 1, chunks from the topic-mixture generator: neighbour gaps of a few 1e-3."""
+    cfg = li.TINY
+    seed = li.config_seed(1) + 100
+    wts = li.encoder_weights(cfg, seed)
+    topics = li.make_topics(1000, 200, 20, seed + 1)
+    tokens, lengths, _ = li.topic_chunks(topics, 2000, 32, 8, 32, seed + 2)
+    qtok, qlen, _ = li.topic_chunks(topics, 24, 32, 8, 32, seed + 3)   # fresh chunks as queries
+    e = orc.desc(**cfg)
+    emb = orc.embed(e, wts, tokens, lengths)
+    queries = orc.embed(e, wts, qtok, qlen)
+    nbr, _ = li.knn_graph(emb, 16)
+    entry, _ = li.max_in_degree_node(nbr)
+    row_ptr, col_idx = li.to_csr(nbr)
+    cb, _ = orc.pq_train(emb, 16, 10, seed + 4)
+    codes = orc.pq_encode(emb, cb)
+    w = dict(cfg=cfg, emb=emb, emb_bf16=orc.embed(e, wts, tokens, lengths, precision=1), queries=queries, row_ptr=row_ptr, col_idx=col_idx, entry=entry, cb=cb, codes=codes)
+    ctx = L.leann_create(cfg, to_dev(wts))
+    pq = L.leann_pq_import(ctx, cb, codes)
+    try:
+        total = 0
+        for ef, k, alpha, batch in ((32, 3, 0.2, 32), (64, 3, 0.5, 8)):
+            total += full_path_case(L, orc, w, ctx, pq, (to_dev(row_ptr), to_dev(col_idx), entry), to_dev(tokens),
+                                    to_dev(lengths), to_dev(queries), ef, k, alpha, batch, "structured tiny")
+        assert total >= 30  # the comparison is not vacuous
+        hits = 0
+        ids, _, _ = L.leann_search(ctx, to_dev(queries), (to_dev(row_ptr), to_dev(col_idx), entry), pq, to_dev(tokens),
+                                   to_dev(lengths), 64, 3, 0.5, 8)
+        for qi in range(len(queries)):
+            hits += len(set(ids[qi].cpu().numpy()) & set(orc.exact_topk(queries[qi], emb, 3)[0]))
+        print(f"structured tiny: recall@3 at ef=64 = {hits / (3 * len(queries)):.3f}")
+    finally:
+        L.leann_pq_free(pq)
+        L.leann_destroy(ctx)
+
+
+def test_exact_topk_when_ef_covers_graph(L, orc, world):
+    """alpha = 1, ef >= N on a strongly connected graph: every node is scored, result = brute force (Eq. 1)."""
+    w = world
+    n = 300
+    say("ef >= N exactness, n=300 ring-augmented graph")
+    emb = w["emb"][:n]
+    nbr, _ = li.knn_graph(emb, 6)
+    row_ptr, col_idx = li.to_csr(li.add_ring(list(nbr)))
+    pq = L.leann_pq_import(w["ctx"], w["cb"], w["codes"][:n])
+    cache = (to_dev(np.arange(n, dtype=np.int32)), to_dev(emb))
+    graph = (to_dev(row_ptr), to_dev(col_idx), 5)
+    q = to_dev(w["queries"][:4])
+    ids, scores, st = L.leann_search(w["ctx"], q, graph, pq, w["t"][:n].contiguous(), w["l"][:n].contiguous(), 300, 7,
+                                     1.0, 13, cache=cache)
+    L.leann_pq_free(pq)
+    for qi in range(4):
+        want_ids, want_sc = orc.exact_topk(w["queries"][qi], emb, 7)
+        assert list(ids[qi].cpu().numpy()) == list(want_ids)
+        np.testing.assert_allclose(scores[qi].cpu().numpy(), want_sc, atol=2e-6)
+    assert st["recomputed_chunks"] == 4 * n
+
+
+def test_unreachable_padding_and_argument_checks(L, world):
+    import torch
+    w = world
+    say("padding with -1 and argument checks")
+    n = 6
+    row_ptr, col_idx = li.to_csr([np.array([1]), np.array([0]), np.array([]), np.array([]), np.array([]), np.array([])])
+    pq = L.leann_pq_import(w["ctx"], w["cb"], w["codes"][:n])
+    graph = (to_dev(row_ptr), to_dev(col_idx), 0)
+    t, l = w["t"][:n].contiguous(), w["l"][:n].contiguous()
+    ids, scores, _ = L.leann_search(w["ctx"], w["q"][:2].contiguous(), graph, pq, t, l, 4, 3, 1.0, 2)
+    ids = ids.cpu().numpy()
+    assert set(ids[0][:2]) == {0, 1} and ids[0][2] == -1 and torch.isinf(scores[0][2])
+    for kw in (dict(ef=2, k=3, a=0.5, b=1), dict(ef=4, k=0, a=0.5, b=1), dict(ef=4, k=3, a=0.0, b=1),
+               dict(ef=4, k=3, a=1.5, b=1), dict(ef=4, k=3, a=0.5, b=0), dict(ef=2000, k=3, a=0.5, b=1)):
+        with pytest.raises(L.LeannError) as ei:
+            L.leann_search(w["ctx"], w["q"], graph, pq, t, l, kw["ef"], kw["k"], kw["a"], kw["b"])
+        assert ei.value.status == -1
+    with pytest.raises(L.LeannError) as ei:  # graph and chunk store disagree
+        L.leann_search(w["ctx"], w["q"], graph, pq, w["t"], w["l"], 4, 3, 0.5, 1)
+    assert ei.value.status == -4
+    bad_col = col_idx.copy()
+    bad_col[0] = 6  # neighbour id outside the graph
+    with pytest.raises(L.LeannError):
+        L.leann_search(w["ctx"], w["q"][:1].contiguous(), (to_dev(row_ptr), to_dev(bad_col), 0), pq, t, l, 4, 3, 1.0, 2)
+    with pytest.raises(L.LeannError):  # entry point outside the graph
+        L.leann_search(w["ctx"], w["q"][:1].contiguous(), (to_dev(row_ptr), to_dev(col_idx), 6), pq, t, l, 4, 3, 1.0, 2)
+    ids0, _, st0 = L.leann_search(w["ctx"], w["q"][:0].contiguous(), graph, pq, t, l, 4, 3, 1.0, 2)
+    assert ids0.shape == (0, 3) and st0["hops"] == 0
+    L.leann_pq_free(pq)
