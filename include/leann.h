@@ -146,10 +146,11 @@ int leann_pq_info(const leann_pq *pq, int64_t *n, int32_t *d, int32_t *m_sub);
 void leann_pq_free(leann_pq *pq);
 
 /*
- * Approximate scores (Alg. 2 "Insert (v, Dist(q, x~_v)) into AQ"): for each query
- * a lookup table lut[m][c] = <q_m, codebook[m][c]> is built (sub-vector summed in
- * index order) and out[i][j] = sum_m lut[m][codes[cand[i][j]][m]] in the fixed order
- * m = 0..m_sub-1, fp32.
+ * Approximate scores (Alg. 2 "Insert (v, Dist(q, x~_v)) into AQ"), product
+ * quantisation's asymmetric distance: for each query a lookup table
+ * lut[m][c] = -|q_m - codebook[m][c]|^2 is built (sub-vector summed in index order)
+ * and out[i][j] = sum_m lut[m][codes[cand[i][j]][m]] in the fixed order m = 0..m_sub-1,
+ * fp32: the negated squared distance between q and the decoded vector (larger is closer).
  *   queries_dev fp32[nq][d]; cand_ids_dev u32[nq][nc]; out_dev fp32[nq][nc].
  * Candidate ids >= n are an error (LEANN_EINVAL, reported after the kernel ran; out_dev
  * then holds -inf at those positions).
@@ -187,6 +188,26 @@ int leann_search(leann_ctx *ctx, const float *queries_dev, int64_t nq, const lea
 /* Tuning knobs (all optional): largest number of tokens one encoder pass holds
  * (workspace size), and the per-query capacity of the approximate queue. */
 int leann_set_limits(leann_ctx *ctx, int64_t max_tokens_per_pass, int32_t aq_capacity);
+
+/*
+ * Per-kernel device timing for the benchmark: between leann_profile_begin and leann_profile_end every kernel
+ * the library launches on this context is bracketed by HIP events on the context's stream.  ms[i] / launches[i]
+ * give summed duration and launch count per kernel family; tokens = valid tokens that went through the encoder,
+ * so that the GEMM work is tokens * layers * 2 * (4*hidden^2 + 2*hidden*ffn) flops.  leann_profile_end
+ * synchronises the stream.
+ */
+enum {
+    LEANN_PROF_GEMM_QKV = 0, LEANN_PROF_GEMM_O, LEANN_PROF_GEMM_FFN1, LEANN_PROF_GEMM_FFN2, LEANN_PROF_ATTENTION,
+    LEANN_PROF_LAYERNORM, LEANN_PROF_ENC_OTHER, LEANN_PROF_TRAVERSE, LEANN_PROF_COLLECT, LEANN_PROF_SCORE_INSERT,
+    LEANN_PROF_LUT, LEANN_PROF_ADC, LEANN_PROF_KINDS
+};
+typedef struct {
+    double ms[LEANN_PROF_KINDS];
+    int64_t launches[LEANN_PROF_KINDS];
+    int64_t tokens;
+} leann_profile;
+int leann_profile_begin(leann_ctx *ctx);
+int leann_profile_end(leann_ctx *ctx, leann_profile *out_host);
 
 #ifdef __cplusplus
 }

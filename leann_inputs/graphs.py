@@ -65,37 +65,82 @@ def add_ring(nbr_lists):
             for i, r in enumerate(nbr_lists)]
 
 
-def hub_prune_fixture(nbr, sim, hub_frac=0.02, hub_deg=64, low_deg=16):
-    """Degree-skewed fixture in the spirit of the paper's high-degree-preserving pruning (Alg. 3).
+def _diversify(emb, nbr, sim, block=8192):
+    """Relative-neighbourhood selection over each node's candidate list (best first): candidate c is kept when it
+    is more similar to the node than to every candidate kept before it.  Returns a bool mask [n][k]."""
+    try:
+        import torch
+    except ImportError:  # pragma: no cover
+        torch = None
+    n, k = nbr.shape
+    keep = np.zeros((n, k), dtype=bool)
+    if torch is not None and isinstance(emb, torch.Tensor):
+        nb = torch.from_numpy(np.ascontiguousarray(nbr)).to(emb.device)
+        sm = torch.from_numpy(np.ascontiguousarray(sim)).to(emb.device)
+        for s in range(0, n, block):
+            e = min(n, s + block)
+            c = emb[nb[s:e]].float()
+            pair = torch.bmm(c, c.transpose(1, 2))
+            kp = torch.zeros((e - s, k), dtype=torch.bool, device=emb.device)
+            for i in range(k):
+                kp[:, i] = ~((pair[:, i, :] >= sm[s:e, i:i + 1]) & kp).any(1)
+            keep[s:e] = kp.cpu().numpy()
+        return keep
+    emb = np.asarray(emb, dtype=np.float32)
+    for s in range(0, n, block):
+        e = min(n, s + block)
+        c = emb[nbr[s:e]]
+        pair = np.einsum("bid,bjd->bij", c, c)
+        kp = np.zeros((e - s, k), dtype=bool)
+        for i in range(k):
+            kp[:, i] = ~((pair[:, i, :] >= sim[s:e, i:i + 1]) & kp).any(1)
+        keep[s:e] = kp
+    return keep
 
-    Hubs = top ceil(hub_frac * n) nodes by in-degree of the kNN graph (ties: lower id).
-    A hub keeps the hub_deg most similar of (its own kNN list + its reverse edges);
-    every other node keeps the first low_deg entries of its own list.
+
+def navigable_fixture(emb, nbr, sim, hub_frac=0.02, hub_deg=64, low_deg=16):
+    """Degree-skewed, navigable graph fixture in the spirit of the paper's high-degree-preserving pruning
+    (Alg. 3: hubs keep up to M edges, other nodes m, edges are added in both directions).
+
+    Hubs = top ceil(hub_frac * n) nodes by in-degree of the kNN graph (ties: lower id).  Every node first takes
+    the relative-neighbourhood-diversified subset of its kNN list (at most its cap), then reverse edges of other
+    nodes' selections, most similar first, while it has room (cap hub_deg for hubs, low_deg otherwise); a node
+    still below low_deg is filled with its nearest unselected kNN entries.
     Returns (list of neighbour arrays, hub ids, in-degree array).
     """
     nbr = np.asarray(nbr)
     sim = np.asarray(sim)
-    n, deg = nbr.shape
+    n, k = nbr.shape
     indeg = np.bincount(nbr.reshape(-1), minlength=n)
     n_hub = int(np.ceil(hub_frac * n))
     hubs = np.lexsort((np.arange(n), -indeg))[:n_hub]
-    is_hub = np.zeros(n, dtype=bool)
-    is_hub[hubs] = True
-    src = np.repeat(np.arange(n, dtype=np.int64), deg)
-    dst = nbr.reshape(-1)
-    s = sim.reshape(-1)
-    sel = is_hub[dst]
-    r_dst, r_src, r_sim = dst[sel], src[sel], s[sel]
-    order = np.argsort(r_dst, kind="stable")
-    r_dst, r_src, r_sim = r_dst[order], r_src[order], r_sim[order]
-    starts = np.searchsorted(r_dst, hubs, side="left")
-    ends = np.searchsorted(r_dst, hubs, side="right")
-    out = [nbr[i, :low_deg].astype(np.int64) for i in range(n)]
-    for h, a, b in zip(hubs, starts, ends):
-        ids = np.concatenate([nbr[h], r_src[a:b]])
-        sc = np.concatenate([sim[h], r_sim[a:b]])
-        ids, first = np.unique(ids, return_index=True)
-        sc = sc[first]
-        keep = np.lexsort((ids, -sc))[:hub_deg]
-        out[h] = ids[keep].astype(np.int64)
+    cap = np.full(n, low_deg, dtype=np.int64)
+    cap[hubs] = hub_deg
+    keep = _diversify(emb, nbr, sim)
+    keep &= np.cumsum(keep, axis=1) <= cap[:, None]
+    src = np.repeat(np.arange(n, dtype=np.int64), k)[keep.reshape(-1)]
+    dst = nbr.reshape(-1)[keep.reshape(-1)]
+    fsim = sim.reshape(-1)[keep.reshape(-1)]
+    order = np.lexsort((src, -fsim, dst))          # reverse edges grouped by target, most similar first
+    r_src, r_dst = src[order], dst[order]
+    starts = np.searchsorted(r_dst, np.arange(n), side="left")
+    ends = np.searchsorted(r_dst, np.arange(n), side="right")
+    out = []
+    for i in range(n):
+        sel = list(nbr[i][keep[i]])
+        have = set(sel)
+        for v in r_src[starts[i]:ends[i]]:
+            if len(sel) >= cap[i]:
+                break
+            if v not in have:
+                sel.append(int(v))
+                have.add(int(v))
+        if len(sel) < low_deg:
+            for v in nbr[i]:
+                if len(sel) >= low_deg:
+                    break
+                if v not in have:
+                    sel.append(int(v))
+                    have.add(int(v))
+        out.append(np.asarray(sel, dtype=np.int64))
     return out, hubs, indeg

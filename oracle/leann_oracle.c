@@ -13,7 +13,8 @@
  *     masked mean pooling and L2 normalisation;
  *   - PQ / ADC: the paper cites product quantisation and only gives its
  *     size (Sec. 3 "Storage composition", Sec. 4.1 "Discussion"); the
- *     textbook train / encode / asymmetric-distance definitions are used;
+ *     textbook train / encode / asymmetric-distance (squared L2)
+ *     definitions are used;
  *   - search: Algorithm 2 (two-level search, Sec. 4.1) with the batching
  *     rule of Sec. 4.2; Algorithm 1 (Sec. 2) is its alpha = 1, batch = 1
  *     special case; Eq. 1 is the exact top-k used as ground truth.
@@ -426,7 +427,14 @@ int orc_pq_decode(const uint8_t *codes, int64_t n, int32_t d, int32_t m_sub, int
     return ORC_OK;
 }
 
-/* lut[m][c] = <q_m, codebook[m][c]>, summed over the sub-vector in index order. */
+/*
+ * Asymmetric distance computation as product quantisation defines it: the squared Euclidean distance
+ * between the un-quantised query and the quantised vector splits over the subspaces, so one table per query,
+ *   lut[m][c] = -|q_m - codebook[m][c]|^2   (sub-vector summed in index order, then negated),
+ * turns Dist(q, x~_v) of Alg. 2 into m_sub lookups.  The sign makes every score in this file "larger is closer";
+ * Eq. 1 states the search in Euclidean distance, and for the unit-norm embeddings used here exact L2 and
+ * exact inner-product rankings coincide.
+ */
 int orc_lut(const float *q, int32_t d, int32_t m_sub, int32_t ksub, const float *codebook, float *lut)
 {
     if (!q || !codebook || !lut || d % m_sub) return ORC_EINVAL;
@@ -434,13 +442,16 @@ int orc_lut(const float *q, int32_t d, int32_t m_sub, int32_t ksub, const float 
     for (int m = 0; m < m_sub; ++m)
         for (int c = 0; c < ksub; ++c) {
             float s = 0.f;
-            for (int j = 0; j < dsub; ++j) s += q[m * dsub + j] * codebook[((int64_t)m * ksub + c) * dsub + j];
-            lut[m * ksub + c] = s;
+            for (int j = 0; j < dsub; ++j) {
+                float t = q[m * dsub + j] - codebook[((int64_t)m * ksub + c) * dsub + j];
+                s += t * t;
+            }
+            lut[m * ksub + c] = -s;
         }
     return ORC_OK;
 }
 
-/* ADC similarity of one code row: sum of table entries in order m = 0..m_sub-1. */
+/* ADC score of one code row: sum of table entries in order m = 0..m_sub-1 (= -|q - decode(code)|^2). */
 static float adc_one(const float *lut, int ksub, const uint8_t *code, int m_sub)
 {
     float s = 0.f;
@@ -448,7 +459,7 @@ static float adc_one(const float *lut, int ksub, const uint8_t *code, int m_sub)
     return s;
 }
 
-/* out[i] = ADC similarity of node ids[i]; l1[i] (nullable) = sum of |terms|. */
+/* out[i] = ADC score of node ids[i]; l1[i] (nullable) = sum of |terms|. */
 int orc_adc(const float *lut, int32_t m_sub, int32_t ksub, const uint8_t *codes, const uint32_t *ids, int64_t n_ids,
             float *out, float *l1)
 {

@@ -20,7 +20,9 @@ STATUS = {0: "LEANN_OK", -1: "LEANN_EINVAL", -2: "LEANN_ENOMEM", -3: "LEANN_EDEV
           -5: "LEANN_ECAPACITY"}
 EXPORTS = ["leann_last_error", "leann_create", "leann_destroy", "leann_embed", "leann_build_pq", "leann_pq_export",
            "leann_pq_import", "leann_pq_wrap", "leann_pq_info", "leann_pq_free", "leann_adc", "leann_search",
-           "leann_set_limits"]
+           "leann_set_limits", "leann_profile_begin", "leann_profile_end"]
+PROF_KINDS = ["gemm_qkv", "gemm_o", "gemm_ffn1", "gemm_ffn2", "attention", "layernorm", "enc_other", "traverse",
+              "collect", "score_insert", "lut", "adc"]
 
 
 class LeannError(RuntimeError):
@@ -54,6 +56,11 @@ class SearchStats(C.Structure):
 
     def as_dict(self):
         return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+class Profile(C.Structure):
+    _fields_ = [("ms", C.c_double * len(PROF_KINDS)), ("launches", C.c_int64 * len(PROF_KINDS)),
+                ("tokens", C.c_int64)]
 
 
 def load_library(path=LIB_PATH):
@@ -220,3 +227,15 @@ def leann_search(ctx, queries, graph, pq, tokens, lengths, ef, k, rerank_ratio, 
                                        C.c_int32(ef), C.c_int32(k), C.c_float(rerank_ratio), C.c_int32(batch),
                                        _ptr(ids), _ptr(scores), C.byref(st)))
     return ids, scores, st.as_dict()
+
+
+def leann_profile_begin(ctx):
+    _check(load_library().leann_profile_begin(ctx))
+
+
+def leann_profile_end(ctx):
+    """Returns {"ms": {kind: summed ms}, "launches": {kind: count}, "tokens": valid tokens encoded}."""
+    p = Profile()
+    _check(load_library().leann_profile_end(ctx, C.byref(p)))
+    return {"ms": {k: p.ms[i] for i, k in enumerate(PROF_KINDS)},
+            "launches": {k: p.launches[i] for i, k in enumerate(PROF_KINDS)}, "tokens": p.tokens}

@@ -40,6 +40,31 @@ void DevBuf::release()
     bytes = 0;
 }
 
+ProfScope::ProfScope(leann_ctx *c, int kind) : ctx(c)
+{
+    if (!c->prof_on) return;
+    hipEvent_t a = nullptr;
+    for (hipEvent_t *e : {&a, &b}) {
+        if (!c->prof_pool.empty()) {
+            *e = c->prof_pool.back();
+            c->prof_pool.pop_back();
+        } else if (hipEventCreate(e) != hipSuccess) {
+            *e = nullptr;
+        }
+    }
+    if (!a || !b) {
+        b = nullptr;
+        return;
+    }
+    (void)hipEventRecord(a, c->stream);
+    c->prof_spans.push_back({kind, a, b});
+}
+
+ProfScope::~ProfScope()
+{
+    if (b) (void)hipEventRecord(b, ctx->stream);
+}
+
 namespace {
 
 __global__ void f32_to_bf16_kernel(const float *__restrict__ in, bf16_t *__restrict__ out, size_t n)
@@ -177,6 +202,12 @@ void leann_destroy(leann_ctx *ctx)
                       &ctx->len, &ctx->meta, &ctx->enc_ids, &ctx->s_state, &ctx->s_emb, &ctx->s_lut, &ctx->s_seen,
                       &ctx->s_misc};
     for (DevBuf *b : bufs) b->release();
+    ctx->prof_tokens.release();
+    for (auto &sp : ctx->prof_spans) {
+        (void)hipEventDestroy(sp.a);
+        (void)hipEventDestroy(sp.b);
+    }
+    for (hipEvent_t e : ctx->prof_pool) (void)hipEventDestroy(e);
     delete ctx;
 }
 
@@ -188,6 +219,49 @@ int leann_set_limits(leann_ctx *ctx, int64_t max_tokens_per_pass, int32_t aq_cap
     }
     if (max_tokens_per_pass > 0) ctx->max_tokens = std::min<int64_t>(max_tokens_per_pass, (int64_t)1 << 22);
     if (aq_capacity > 0) ctx->aq_capacity = aq_capacity;
+    return LEANN_OK;
+}
+
+int leann_profile_begin(leann_ctx *ctx)
+{
+    if (!ctx) {
+        leann_set_error("leann_profile_begin: null context");
+        return LEANN_EINVAL;
+    }
+    LEANN_HIP(hipSetDevice(ctx->device));
+    LEANN_TRY(ctx->prof_tokens.reserve(sizeof(int64_t)));
+    LEANN_HIP(hipMemsetAsync(ctx->prof_tokens.p, 0, sizeof(int64_t), ctx->stream));
+    for (auto &sp : ctx->prof_spans) {
+        ctx->prof_pool.push_back(sp.a);
+        ctx->prof_pool.push_back(sp.b);
+    }
+    ctx->prof_spans.clear();
+    ctx->prof_on = true;
+    return LEANN_OK;
+}
+
+int leann_profile_end(leann_ctx *ctx, leann_profile *out_host)
+{
+    if (!ctx || !out_host) {
+        leann_set_error("leann_profile_end: null argument");
+        return LEANN_EINVAL;
+    }
+    LEANN_HIP(hipSetDevice(ctx->device));
+    ctx->prof_on = false;
+    *out_host = leann_profile{};
+    LEANN_HIP(hipStreamSynchronize(ctx->stream));
+    if (ctx->prof_tokens.p)
+        LEANN_HIP(hipMemcpy(&out_host->tokens, ctx->prof_tokens.p, sizeof(int64_t), hipMemcpyDeviceToHost));
+    for (auto &sp : ctx->prof_spans) {
+        float t = 0.f;
+        if (hipEventElapsedTime(&t, sp.a, sp.b) == hipSuccess) {
+            out_host->ms[sp.kind] += t;
+            out_host->launches[sp.kind] += 1;
+        }
+        ctx->prof_pool.push_back(sp.a);
+        ctx->prof_pool.push_back(sp.b);
+    }
+    ctx->prof_spans.clear();
     return LEANN_OK;
 }
 

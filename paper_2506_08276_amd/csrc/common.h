@@ -13,6 +13,7 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 void leann_set_error(const char *fmt, ...);
 
@@ -61,7 +62,23 @@ struct leann_ctx {
     DevBuf x, qkv, att, pre, hid, cu, len, meta, enc_ids;
     // search workspace
     DevBuf s_state, s_emb, s_lut, s_seen, s_misc;
-    hipEvent_t ev[8] = {};
+    // optional per-kernel timing (leann_profile_begin / leann_profile_end)
+    bool prof_on = false;
+    DevBuf prof_tokens;  // device int64: valid tokens sent through the encoder while profiling
+    struct ProfSpan {
+        int kind;
+        hipEvent_t a, b;
+    };
+    std::vector<ProfSpan> prof_spans;
+    std::vector<hipEvent_t> prof_pool;
+};
+
+// Brackets one kernel launch with HIP events on the context's stream when profiling is on.
+struct ProfScope {
+    leann_ctx *ctx;
+    hipEvent_t b = nullptr;
+    ProfScope(leann_ctx *c, int kind);
+    ~ProfScope();
 };
 
 struct leann_pq {

@@ -21,7 +21,8 @@ __device__ inline float wave_sum(float v)
 __global__ __launch_bounds__(1024) void prep_kernel(const int32_t *__restrict__ lengths, const int64_t *__restrict__ ids,
                                                     int64_t first_id, int n, int64_t n_store, int seq,
                                                     int32_t *__restrict__ cu, int64_t *__restrict__ chunk_of,
-                                                    int *__restrict__ err, int64_t *__restrict__ tok_count)
+                                                    int *__restrict__ err, int64_t *__restrict__ tok_count,
+                                                    int64_t *__restrict__ tok_count2)
 {
     __shared__ int part[1024];
     const int tid = threadIdx.x;
@@ -62,6 +63,7 @@ __global__ __launch_bounds__(1024) void prep_kernel(const int32_t *__restrict__ 
     if (tid == 1023) {
         cu[n] = part[1023];
         if (tok_count) *tok_count += part[1023];
+        if (tok_count2) *tok_count2 += part[1023];
     }
 }
 
@@ -184,33 +186,24 @@ __global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ A,
 
     const bf16_t *Ag = A + (size_t)tile_m * BM * K;
     const bf16_t *Wg = W + (size_t)tile_n * BN * K;
-    constexpr int ACH = BM * 8 / 256, BCH = BN * 8 / 256;
-    uint4 ra[ACH], rb[BCH];
+    constexpr int ACH = BM * 8 / 256, BCH = BN * 8 / 256;  // 16-byte chunks per thread and K-slab
+    u32x4 ra[ACH], rb[BCH];
+    // thread -> (row, chunk) of the slab: 8 consecutive threads cover one 128-byte row segment
+    const int lrow = tid >> 3, lc = tid & 7;
+    const bf16_t *ag = Ag + (size_t)lrow * K + lc * 8;
+    const bf16_t *wg = Wg + (size_t)lrow * K + lc * 8;
+    const int soff = lrow * 64 + ((lc ^ ((lrow >> 1) & 7)) << 3);  // rows 32 apart share the swizzle term
 
-    auto gload = [&](int k0) {
-#pragma unroll
-        for (int i = 0; i < ACH; ++i) {
-            int ci = tid + 256 * i, row = ci >> 3, c = ci & 7;
-            ra[i] = *reinterpret_cast<const uint4 *>(Ag + (size_t)row * K + k0 + c * 8);
-        }
-#pragma unroll
-        for (int i = 0; i < BCH; ++i) {
-            int ci = tid + 256 * i, row = ci >> 3, c = ci & 7;
-            rb[i] = *reinterpret_cast<const uint4 *>(Wg + (size_t)row * K + k0 + c * 8);
-        }
-    };
-    auto sstore = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < ACH; ++i) {
-            int ci = tid + 256 * i, row = ci >> 3, c = ci & 7;
-            *reinterpret_cast<uint4 *>(As + buf * BM * 64 + row * 64 + ((c ^ ((row >> 1) & 7)) << 3)) = ra[i];
-        }
-#pragma unroll
-        for (int i = 0; i < BCH; ++i) {
-            int ci = tid + 256 * i, row = ci >> 3, c = ci & 7;
-            *reinterpret_cast<uint4 *>(Bs + buf * BN * 64 + row * 64 + ((c ^ ((row >> 1) & 7)) << 3)) = rb[i];
-        }
-    };
+#define GEMM_GLOAD(k0)                                                                                   \
+    _Pragma("unroll") for (int i = 0; i < ACH; ++i)                                                      \
+        ra[i] = *reinterpret_cast<const u32x4 *>(ag + (size_t)(32 * i) * K + (k0));                       \
+    _Pragma("unroll") for (int i = 0; i < BCH; ++i)                                                      \
+        rb[i] = *reinterpret_cast<const u32x4 *>(wg + (size_t)(32 * i) * K + (k0));
+#define GEMM_SSTORE(buf)                                                                                 \
+    _Pragma("unroll") for (int i = 0; i < ACH; ++i)                                                      \
+        *reinterpret_cast<u32x4 *>(As + (buf) * BM * 64 + 32 * 64 * i + soff) = ra[i];                    \
+    _Pragma("unroll") for (int i = 0; i < BCH; ++i)                                                      \
+        *reinterpret_cast<u32x4 *>(Bs + (buf) * BN * 64 + 32 * 64 * i + soff) = rb[i];
 
     f32x16 acc[TM][TN];
 #pragma unroll
@@ -220,12 +213,15 @@ __global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ A,
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
 
+    // The prefetch of the next K-slab and its LDS store are unconditional (the last iteration re-reads the last
+    // slab into the idle stage): no branch in the loop body, so the staging registers stay registers.
     const int KT = K >> 6;
-    gload(0);
-    sstore(0);
+    GEMM_GLOAD(0)
+    GEMM_SSTORE(0)
     __syncthreads();
     for (int kt = 0; kt < KT; ++kt) {
-        if (kt + 1 < KT) gload((kt + 1) << 6);
+        const int knext = min(kt + 1, KT - 1) << 6;
+        GEMM_GLOAD(knext)
         const bf16_t *as = As + (kt & 1) * BM * 64;
         const bf16_t *bs = Bs + (kt & 1) * BN * 64;
 #pragma unroll
@@ -248,10 +244,12 @@ __global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ A,
                 for (int ni = 0; ni < TN; ++ni)
                     acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[ni], acc[mi][ni], 0, 0, 0);
         }
-        if (kt + 1 < KT) sstore((kt + 1) & 1);
+        GEMM_SSTORE((kt + 1) & 1)
         __syncthreads();
     }
 
+#undef GEMM_GLOAD
+#undef GEMM_SSTORE
     // accumulator register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32 of its 32x32 tile
 #pragma unroll
     for (int mi = 0; mi < TM; ++mi)
@@ -440,7 +438,7 @@ __global__ __launch_bounds__(256) void pool_kernel(const bf16_t *__restrict__ x,
 }
 
 template <int BM, int BN, int EPI>
-int launch_gemm(leann_ctx *ctx, const bf16_t *A, const bf16_t *W, const float *bias, const bf16_t *res, void *out,
+int launch_gemm(leann_ctx *ctx, int prof_kind, const bf16_t *A, const bf16_t *W, const float *bias, const bf16_t *res, void *out,
                 const int32_t *T_dev, int max_rows, int N, int K)
 {
     static bool attr_done = false;
@@ -453,6 +451,7 @@ int launch_gemm(leann_ctx *ctx, const bf16_t *A, const bf16_t *W, const float *b
     const int tiles_n = N / BN;
     const int tiles = ((max_rows + BM - 1) / BM) * tiles_n;
     const int grid = (tiles + 7) & ~7;
+    ProfScope prof(ctx, prof_kind);
     hipLaunchKernelGGL((gemm_kernel<BM, BN, EPI>), dim3(grid), dim3(256), smem, ctx->stream, A, W, bias, res, out, T_dev,
                        N, K, tiles_n);
     LEANN_HIP(hipGetLastError());
@@ -498,27 +497,45 @@ int enc_forward(leann_ctx *ctx, const leann_chunks *chunks, const int64_t *ids_d
         const int m = (int)((n - s < per_pass) ? n - s : per_pass);
         const int max_rows = m * seq;
         const int32_t *T_dev = cu + m;
-        hipLaunchKernelGGL(prep_kernel, dim3(1), dim3(1024), 0, ctx->stream, chunks->lengths,
-                           ids_dev ? ids_dev + s : nullptr, first_id + s, m, chunks->n, seq, cu, chunk_of, err_dev,
-                           tok_count_dev);
-        hipLaunchKernelGGL(embed_ln_kernel, dim3((unsigned)(((int64_t)m * seq + 3) / 4)), dim3(256), 0, ctx->stream,
-                           chunks->tokens, chunk_of, cu, m, seq, d, e.vocab, ctx->tok_emb, ctx->pos_emb, ctx->seg_emb,
-                           ctx->emb_g, ctx->emb_b, e.ln_eps, x, err_dev);
+        {
+            ProfScope prof(ctx, LEANN_PROF_ENC_OTHER);
+            hipLaunchKernelGGL(prep_kernel, dim3(1), dim3(1024), 0, ctx->stream, chunks->lengths,
+                               ids_dev ? ids_dev + s : nullptr, first_id + s, m, chunks->n, seq, cu, chunk_of, err_dev,
+                               tok_count_dev, ctx->prof_on ? (int64_t *)ctx->prof_tokens.p : nullptr);
+        }
+        {
+            ProfScope prof(ctx, LEANN_PROF_ENC_OTHER);
+            hipLaunchKernelGGL(embed_ln_kernel, dim3((unsigned)(((int64_t)m * seq + 3) / 4)), dim3(256), 0, ctx->stream,
+                               chunks->tokens, chunk_of, cu, m, seq, d, e.vocab, ctx->tok_emb, ctx->pos_emb, ctx->seg_emb,
+                               ctx->emb_g, ctx->emb_b, e.ln_eps, x, err_dev);
+        }
         const int ln_grid = (max_rows + 3) / 4;
+        auto layer_norm = [&](const float *g, const float *b) {
+            ProfScope prof(ctx, LEANN_PROF_LAYERNORM);
+            hipLaunchKernelGGL(ln_kernel, dim3(ln_grid), dim3(256), 0, ctx->stream, pre, g, b, x, T_dev, d, e.ln_eps);
+        };
         for (int l = 0; l < e.layers; ++l) {
             const LayerWeights &w = ctx->layers[l];
-            LEANN_TRY((launch_gemm<128, 128, EPI_BIAS>(ctx, x, w.wqkv, w.bqkv, nullptr, qkv, T_dev, max_rows, 3 * d, d)));
-            hipLaunchKernelGGL(attention_kernel, dim3(m, H), dim3(256), ATT_SMEM, ctx->stream, qkv, cu, att, d,
-                               scale_log2e);
-            LEANN_TRY((launch_gemm<128, 128, EPI_BIAS_RES_F32>(ctx, att, w.wo, w.bo, x, pre, T_dev, max_rows, d, d)));
-            hipLaunchKernelGGL(ln_kernel, dim3(ln_grid), dim3(256), 0, ctx->stream, pre, w.g1, w.be1, x, T_dev, d,
-                               e.ln_eps);
-            LEANN_TRY((launch_gemm<128, 128, EPI_BIAS_GELU>(ctx, x, w.w1, w.b1, nullptr, hid, T_dev, max_rows, F, d)));
-            LEANN_TRY((launch_gemm<128, 128, EPI_BIAS_RES_F32>(ctx, hid, w.w2, w.b2, x, pre, T_dev, max_rows, d, F)));
-            hipLaunchKernelGGL(ln_kernel, dim3(ln_grid), dim3(256), 0, ctx->stream, pre, w.g2, w.be2, x, T_dev, d,
-                               e.ln_eps);
+            LEANN_TRY((launch_gemm<128, 128, EPI_BIAS>(ctx, LEANN_PROF_GEMM_QKV, x, w.wqkv, w.bqkv, nullptr, qkv, T_dev,
+                                                       max_rows, 3 * d, d)));
+            {
+                ProfScope prof(ctx, LEANN_PROF_ATTENTION);
+                hipLaunchKernelGGL(attention_kernel, dim3(m, H), dim3(256), ATT_SMEM, ctx->stream, qkv, cu, att, d,
+                                   scale_log2e);
+            }
+            LEANN_TRY((launch_gemm<128, 128, EPI_BIAS_RES_F32>(ctx, LEANN_PROF_GEMM_O, att, w.wo, w.bo, x, pre, T_dev,
+                                                               max_rows, d, d)));
+            layer_norm(w.g1, w.be1);
+            LEANN_TRY((launch_gemm<128, 128, EPI_BIAS_GELU>(ctx, LEANN_PROF_GEMM_FFN1, x, w.w1, w.b1, nullptr, hid, T_dev,
+                                                            max_rows, F, d)));
+            LEANN_TRY((launch_gemm<128, 128, EPI_BIAS_RES_F32>(ctx, LEANN_PROF_GEMM_FFN2, hid, w.w2, w.b2, x, pre, T_dev,
+                                                               max_rows, d, F)));
+            layer_norm(w.g2, w.be2);
         }
-        hipLaunchKernelGGL(pool_kernel, dim3(m), dim3(256), 0, ctx->stream, x, cu, d, out_dev + (size_t)s * d);
+        {
+            ProfScope prof(ctx, LEANN_PROF_ENC_OTHER);
+            hipLaunchKernelGGL(pool_kernel, dim3(m), dim3(256), 0, ctx->stream, x, cu, d, out_dev + (size_t)s * d);
+        }
         LEANN_HIP(hipGetLastError());
     }
     return LEANN_OK;

@@ -99,7 +99,8 @@ __global__ __launch_bounds__(256) void update_kernel(const float *__restrict__ x
     }
 }
 
-// lut[q][m][c] = <q_m, codebook[m][c]>, sub-vector summed in index order.  grid (nq, m_sub), 256 threads.
+// lut[q][m][c] = -|q_m - codebook[m][c]|^2 (PQ's asymmetric distance, negated so that larger is closer),
+// sub-vector summed in index order.  grid (nq, m_sub), 256 threads.
 __global__ __launch_bounds__(256) void lut_kernel(const float *__restrict__ queries, int d, int m_sub,
                                                   const float *__restrict__ codebook, float *__restrict__ lut)
 {
@@ -109,8 +110,11 @@ __global__ __launch_bounds__(256) void lut_kernel(const float *__restrict__ quer
     __syncthreads();
     const float *cb = codebook + ((size_t)m * KSUB + c) * dsub;
     float s = 0.f;
-    for (int j = 0; j < dsub; ++j) s += qs[j] * cb[j];
-    lut[((size_t)q * m_sub + m) * KSUB + c] = s;
+    for (int j = 0; j < dsub; ++j) {
+        const float t = qs[j] - cb[j];
+        s += t * t;
+    }
+    lut[((size_t)q * m_sub + m) * KSUB + c] = -s;
 }
 
 // out[q][j] = sum_m lut[q][m][codes[cand[q][j]][m]], m ascending.  grid (nq, ceil(nc / 1024)), 256 threads;
@@ -192,6 +196,7 @@ int alloc_pq(leann_ctx *ctx, int64_t n, int32_t d, int32_t m_sub, bool own_codes
 int pq_build_lut(leann_ctx *ctx, const float *queries_dev, int64_t nq, const leann_pq *pq, float *lut_dev)
 {
     if (nq <= 0) return LEANN_OK;
+    ProfScope prof(ctx, LEANN_PROF_LUT);
     hipLaunchKernelGGL(lut_kernel, dim3((unsigned)nq, pq->m_sub), dim3(256), 0, ctx->stream, queries_dev, pq->d,
                        pq->m_sub, pq->codebook, lut_dev);
     LEANN_HIP(hipGetLastError());
@@ -380,8 +385,11 @@ int leann_adc(leann_ctx *ctx, const float *queries_dev, int64_t nq, const leann_
         leann_set_error("lookup table of %d bytes does not fit the ADC kernel's LDS budget", smem);
         return LEANN_ESHAPE;
     }
-    hipLaunchKernelGGL(adc_kernel, dim3((unsigned)nq, (nc + 1023) / 1024), dim3(256), smem, ctx->stream,
-                       (const float *)ctx->s_lut.p, pq->codes, pq->n, pq->m_sub, cand_ids_dev, nc, out_dev, err);
+    {
+        ProfScope prof(ctx, LEANN_PROF_ADC);
+        hipLaunchKernelGGL(adc_kernel, dim3((unsigned)nq, (nc + 1023) / 1024), dim3(256), smem, ctx->stream,
+                           (const float *)ctx->s_lut.p, pq->codes, pq->n, pq->m_sub, cand_ids_dev, nc, out_dev, err);
+    }
     LEANN_HIP(hipGetLastError());
     int herr = 0;
     LEANN_HIP(hipMemcpyAsync(&herr, err, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));

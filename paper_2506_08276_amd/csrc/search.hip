@@ -504,10 +504,16 @@ int search_run(leann_ctx *ctx, const float *queries_dev, int64_t nq, const leann
         LEANN_TRY(pq_build_lut(ctx, qg, g, pq, (float *)ctx->s_lut.p));
         for (;;) {
             LEANN_TRY(mark());
-            hipLaunchKernelGGL(traverse_kernel, dim3(g), dim3(64), trav_smem, st, s, graph->row_ptr, graph->col_idx, n,
-                               pq->codes, m_sub, alpha, batch);
+            {
+                ProfScope prof(ctx, LEANN_PROF_TRAVERSE);
+                hipLaunchKernelGGL(traverse_kernel, dim3(g), dim3(64), trav_smem, st, s, graph->row_ptr, graph->col_idx,
+                                   n, pq->codes, m_sub, alpha, batch);
+            }
             LEANN_HIP(hipMemsetAsync(&counters[CTR_PENDING], 0, 2 * sizeof(long long), st));
-            hipLaunchKernelGGL(collect_kernel, dim3(1), dim3(1024), 0, st, s, g, cache ? cache->slot_of : nullptr);
+            {
+                ProfScope prof(ctx, LEANN_PROF_COLLECT);
+                hipLaunchKernelGGL(collect_kernel, dim3(1), dim3(1024), 0, st, s, g, cache ? cache->slot_of : nullptr);
+            }
             LEANN_HIP(hipMemcpyAsync(h_ctr, counters, sizeof(h_ctr), hipMemcpyDeviceToHost, st));
             LEANN_TRY(mark());
             LEANN_HIP(hipStreamSynchronize(st));
@@ -531,8 +537,11 @@ int search_run(leann_ctx *ctx, const float *queries_dev, int64_t nq, const leann
                 if (rc != LEANN_OK) break;
                 encoded += n_enc;
             }
-            hipLaunchKernelGGL(score_insert_kernel, dim3(g), dim3(64), eq_smem, st, s, qg, d, (const float *)ctx->s_emb.p,
-                               cache ? cache->emb : nullptr);
+            {
+                ProfScope prof(ctx, LEANN_PROF_SCORE_INSERT);
+                hipLaunchKernelGGL(score_insert_kernel, dim3(g), dim3(64), eq_smem, st, s, qg, d,
+                                   (const float *)ctx->s_emb.p, cache ? cache->emb : nullptr);
+            }
             ++rounds;
         }
         if (rc != LEANN_OK) break;

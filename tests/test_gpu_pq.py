@@ -1,7 +1,7 @@
 """GPU parity: leann_adc / leann_build_pq / PQ import-export against the PQ oracle.
 
-ADC bound (spec: 1e-4 relative): |gpu - oracle| <= 1e-4 * max(|oracle|, sum_m |lut term|), the forward-error
-scale of the sum.  k-means itself is not compared bit for bit (Lloyd iterations amplify rounding); the built table
+ADC bound (spec: 1e-4 relative): |gpu - oracle| <= 1e-4 * |oracle| (every term of the sum has the same
+sign, so the sum's own magnitude is its forward-error scale).  k-means itself is not compared bit for bit (Lloyd iterations amplify rounding); the built table
 is judged by its invariants and by its quantisation error against the oracle's.
 """
 import numpy as np

@@ -20,7 +20,7 @@ def data(n, d, seed, clusters=0):
     return rng.standard_normal((n, d)).astype(np.float32)
 
 
-def test_adc_equals_inner_product_with_decoded_vector(orc):
+def test_adc_equals_negated_squared_distance_to_decoded_vector(orc):
     x = data(600, 32, 0)
     cb, _ = orc.pq_train(x, 4, 5, 7)
     codes = orc.pq_encode(x, cb)
@@ -30,12 +30,20 @@ def test_adc_equals_inner_product_with_decoded_vector(orc):
     for qi in q:
         lut = orc.lut(qi, cb)
         s, l1 = orc.adc(lut, codes, ids)
-        want = dec[ids].astype(np.float64) @ qi.astype(np.float64)
-        assert np.abs(s - want).max() <= 1e-6 * np.abs(l1).max() * 32
-        assert np.all(l1 >= np.abs(s) - 1e-6)
-    # lut entries themselves: <q_m, centroid>
-    want_lut = np.einsum("mj,mcj->mc", q[0].reshape(4, 8).astype(np.float64), cb.astype(np.float64))
-    np.testing.assert_allclose(orc.lut(q[0], cb), want_lut, atol=1e-5)
+        want = -((dec[ids].astype(np.float64) - qi.astype(np.float64)) ** 2).sum(1)
+        assert np.abs(s - want).max() <= 1e-6 * np.abs(want).max()
+        np.testing.assert_allclose(l1, -s, rtol=1e-6)  # every term has the same sign
+    # lut entries themselves: -|q_m - centroid|^2
+    diff = q[0].reshape(4, 1, 8).astype(np.float64) - cb.astype(np.float64)
+    np.testing.assert_allclose(orc.lut(q[0], cb), -(diff ** 2).sum(-1), rtol=1e-5, atol=1e-6)
+    # sign and transposition check on a hand case: q = (1,2 | 0,0), centroid 0 of both subspaces at the origin,
+    # centroid 1 of subspace 0 at (1,2)
+    cb2 = np.zeros((2, 256, 2), np.float32)
+    cb2[0, 1] = [1.0, 2.0]
+    lut2 = orc.lut(np.array([1.0, 2.0, 0.0, 0.0], np.float32), cb2)
+    assert lut2[0, 0] == -5.0 and lut2[0, 1] == 0.0 and lut2[1, 0] == 0.0
+    s2, _ = orc.adc(lut2, np.array([[0, 0], [1, 0]], np.uint8), np.array([0, 1], np.uint32))
+    assert list(s2) == [-5.0, 0.0]
 
 
 def test_decode_layout_and_code_is_true_argmin(orc):
@@ -70,7 +78,13 @@ def test_enough_centroids_means_zero_error(orc):
     np.testing.assert_array_equal(orc.pq_decode(codes, cb), x)
     q = rng.standard_normal(16).astype(np.float32)
     s, _ = orc.adc(orc.lut(q, cb), codes, np.arange(300, dtype=np.uint32))
-    np.testing.assert_allclose(s, x.astype(np.float64) @ q.astype(np.float64), atol=1e-5)
+    np.testing.assert_allclose(s, -((x.astype(np.float64) - q.astype(np.float64)) ** 2).sum(1), rtol=1e-5)
+    # for unit vectors the ADC score is then 2<q,x> - 2: the same ranking as the inner product
+    xu = x / np.linalg.norm(x, axis=1, keepdims=True)
+    qu = q / np.linalg.norm(q)
+    cbu, _ = orc.pq_train(xu, 2, 6, 9)
+    su, _ = orc.adc(orc.lut(qu, cbu), orc.pq_encode(xu, cbu), np.arange(300, dtype=np.uint32))
+    np.testing.assert_allclose(su, 2 * (xu.astype(np.float64) @ qu.astype(np.float64)) - 2, atol=1e-5)
 
 
 def test_single_centroid_is_the_mean(orc):

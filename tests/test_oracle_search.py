@@ -91,7 +91,7 @@ def test_hand_traced_example(orc, case):
     table = np.array([[x, 0.5] for x in exact], np.float32)
     cb = np.zeros((1, 256, 2), np.float32)
     cb[0, :7, 0] = approx
-    cb[0, :7, 1] = 3.0                     # second coordinate is invisible to q = (1, 0)
+    cb[0, :7, 1] = 3.0                     # same offset for every node: ADC order = order of the first coordinate
     codes = np.arange(7, dtype=np.uint8).reshape(7, 1)
     adj = [[1, 2, 3], [4, 0], [5, 6], [4], [3], [], []]
     row_ptr, col_idx = li.to_csr([np.array(a, np.int64) for a in adj])
