@@ -5,7 +5,10 @@
 // Tokens of all chunks of a pass are packed back to back (no padding rows): chunk i owns rows
 // cu[i] .. cu[i+1] of every activation matrix.  The number of valid rows T is only known on the device,
 // so grids are sized for the worst case and blocks beyond T leave at once.
+#include <stdlib.h>
+
 #include "common.h"
+#include "gemm.h"
 
 namespace {
 
@@ -148,128 +151,6 @@ __global__ __launch_bounds__(256) void ln_kernel(const float *__restrict__ in, c
         if (j < per) {
             int c = j * 64 + lane;
             orow[c] = (bf16_t)((v[j] - mean) * inv * g[c] + b[c]);
-        }
-}
-
-// ------------------------------------------------------------------ GEMM
-// C[T][N] = A[T][K] * W[N][K]^T (+ epilogue).  bf16 operands, fp32 accumulation in MFMA 32x32x16.
-// Block tile BM x BN x 64, four waves in a 2x2 grid, two LDS stages.  A 64-element K-slab of a row is
-// eight 16-byte chunks; chunk c of row r lives at chunk position c ^ ((r >> 1) & 7) so that both the
-// row-wise stores and the column-of-rows MFMA operand reads spread over all banks.
-// Each output element is one fixed-order sum over K: a row's result does not depend on T.
-enum { EPI_BIAS = 0, EPI_BIAS_GELU = 1, EPI_BIAS_RES_F32 = 2 };
-
-__device__ inline float gelu_erf(float v) { return 0.5f * v * (1.0f + erff(v * 0.70710678118654752440f)); }
-
-template <int BM, int BN, int EPI>
-__global__ __launch_bounds__(256) void gemm_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W,
-                                                   const float *__restrict__ bias, const bf16_t *__restrict__ res,
-                                                   void *__restrict__ out, const int32_t *__restrict__ T_dev, int N, int K,
-                                                   int tiles_n)
-{
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    bf16_t *As = reinterpret_cast<bf16_t *>(smem);
-    bf16_t *Bs = As + 2 * BM * 64;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave >> 1, wn = wave & 1;
-    constexpr int TM = BM / 64, TN = BN / 64;
-
-    // Blocks go round-robin to the 8 XCDs; give each XCD a contiguous run of tiles (same A rows, all
-    // column tiles) so that the A slab is reused out of that XCD's L2.
-    const int T = *T_dev;
-    const int n_tiles = ((T + BM - 1) / BM) * tiles_n;
-    const int nb = (n_tiles + 7) & ~7;
-    if ((int)blockIdx.x >= nb) return;
-    const int logical = (blockIdx.x & 7) * (nb >> 3) + (blockIdx.x >> 3);
-    if (logical >= n_tiles) return;
-    const int tile_m = logical / tiles_n, tile_n = logical % tiles_n;
-
-    const bf16_t *Ag = A + (size_t)tile_m * BM * K;
-    const bf16_t *Wg = W + (size_t)tile_n * BN * K;
-    constexpr int ACH = BM * 8 / 256, BCH = BN * 8 / 256;  // 16-byte chunks per thread and K-slab
-    u32x4 ra[ACH], rb[BCH];
-    // thread -> (row, chunk) of the slab: 8 consecutive threads cover one 128-byte row segment
-    const int lrow = tid >> 3, lc = tid & 7;
-    const bf16_t *ag = Ag + (size_t)lrow * K + lc * 8;
-    const bf16_t *wg = Wg + (size_t)lrow * K + lc * 8;
-    const int soff = lrow * 64 + ((lc ^ ((lrow >> 1) & 7)) << 3);  // rows 32 apart share the swizzle term
-
-#define GEMM_GLOAD(k0)                                                                                   \
-    _Pragma("unroll") for (int i = 0; i < ACH; ++i)                                                      \
-        ra[i] = *reinterpret_cast<const u32x4 *>(ag + (size_t)(32 * i) * K + (k0));                       \
-    _Pragma("unroll") for (int i = 0; i < BCH; ++i)                                                      \
-        rb[i] = *reinterpret_cast<const u32x4 *>(wg + (size_t)(32 * i) * K + (k0));
-#define GEMM_SSTORE(buf)                                                                                 \
-    _Pragma("unroll") for (int i = 0; i < ACH; ++i)                                                      \
-        *reinterpret_cast<u32x4 *>(As + (buf) * BM * 64 + 32 * 64 * i + soff) = ra[i];                    \
-    _Pragma("unroll") for (int i = 0; i < BCH; ++i)                                                      \
-        *reinterpret_cast<u32x4 *>(Bs + (buf) * BN * 64 + 32 * 64 * i + soff) = rb[i];
-
-    f32x16 acc[TM][TN];
-#pragma unroll
-    for (int mi = 0; mi < TM; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < TN; ++ni)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
-
-    // The prefetch of the next K-slab and its LDS store are unconditional (the last iteration re-reads the last
-    // slab into the idle stage): no branch in the loop body, so the staging registers stay registers.
-    const int KT = K >> 6;
-    GEMM_GLOAD(0)
-    GEMM_SSTORE(0)
-    __syncthreads();
-    for (int kt = 0; kt < KT; ++kt) {
-        const int knext = min(kt + 1, KT - 1) << 6;
-        GEMM_GLOAD(knext)
-        const bf16_t *as = As + (kt & 1) * BM * 64;
-        const bf16_t *bs = Bs + (kt & 1) * BN * 64;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            bf16x8 af[TM], bfr[TN];
-            const int c = ks * 2 + (lane >> 5);
-#pragma unroll
-            for (int mi = 0; mi < TM; ++mi) {
-                int row = wm * (BM / 2) + mi * 32 + (lane & 31);
-                af[mi] = *reinterpret_cast<const bf16x8 *>(as + row * 64 + ((c ^ ((row >> 1) & 7)) << 3));
-            }
-#pragma unroll
-            for (int ni = 0; ni < TN; ++ni) {
-                int row = wn * (BN / 2) + ni * 32 + (lane & 31);
-                bfr[ni] = *reinterpret_cast<const bf16x8 *>(bs + row * 64 + ((c ^ ((row >> 1) & 7)) << 3));
-            }
-#pragma unroll
-            for (int mi = 0; mi < TM; ++mi)
-#pragma unroll
-                for (int ni = 0; ni < TN; ++ni)
-                    acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[mi], bfr[ni], acc[mi][ni], 0, 0, 0);
-        }
-        GEMM_SSTORE((kt + 1) & 1)
-        __syncthreads();
-    }
-
-#undef GEMM_GLOAD
-#undef GEMM_SSTORE
-    // accumulator register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32 of its 32x32 tile
-#pragma unroll
-    for (int mi = 0; mi < TM; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < TN; ++ni) {
-            const int col = tile_n * BN + wn * (BN / 2) + ni * 32 + (lane & 31);
-            const float bv = bias[col];
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = tile_m * BM + wm * (BM / 2) + mi * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                const size_t o = (size_t)row * N + col;
-                float v = acc[mi][ni][r] + bv;
-                if (EPI == EPI_BIAS) {
-                    reinterpret_cast<bf16_t *>(out)[o] = (bf16_t)v;
-                } else if (EPI == EPI_BIAS_GELU) {
-                    reinterpret_cast<bf16_t *>(out)[o] = (bf16_t)gelu_erf(v);
-                } else {
-                    reinterpret_cast<float *>(out)[o] = v + (float)res[o];
-                }
-            }
         }
 }
 
@@ -438,13 +319,18 @@ __global__ __launch_bounds__(256) void pool_kernel(const bf16_t *__restrict__ x,
 }
 
 template <int BM, int BN, int EPI>
-int launch_gemm(leann_ctx *ctx, int prof_kind, const bf16_t *A, const bf16_t *W, const float *bias, const bf16_t *res, void *out,
-                const int32_t *T_dev, int max_rows, int N, int K)
+int launch_gemm(leann_ctx *ctx, int prof_kind, const bf16_t *A, const bf16_t *W, const float *bias, const bf16_t *res,
+                void *out, const int32_t *T_dev, int max_rows, int N, int K)
 {
     static bool attr_done = false;
-    constexpr int smem = 2 * (BM + BN) * 64 * (int)sizeof(bf16_t);
+    constexpr int WM = 2, WN = (BM * BN <= 128 * 128) ? 2 : 4;
+    constexpr int smem = 3 * (BM + BN) * GEMM_BK * (int)sizeof(bf16_t);
+    if (N % BN || K % (4 * GEMM_BK)) {
+        leann_set_error("GEMM shape N=%d K=%d not covered by the %dx%d tile", N, K, BM, BN);
+        return LEANN_ESHAPE;
+    }
     if (!attr_done) {
-        LEANN_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_kernel<BM, BN, EPI>),
+        LEANN_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_kernel<BM, BN, WM, WN, EPI>),
                                       hipFuncAttributeMaxDynamicSharedMemorySize, smem));
         attr_done = true;
     }
@@ -452,8 +338,8 @@ int launch_gemm(leann_ctx *ctx, int prof_kind, const bf16_t *A, const bf16_t *W,
     const int tiles = ((max_rows + BM - 1) / BM) * tiles_n;
     const int grid = (tiles + 7) & ~7;
     ProfScope prof(ctx, prof_kind);
-    hipLaunchKernelGGL((gemm_kernel<BM, BN, EPI>), dim3(grid), dim3(256), smem, ctx->stream, A, W, bias, res, out, T_dev,
-                       N, K, tiles_n);
+    hipLaunchKernelGGL((gemm_kernel<BM, BN, WM, WN, EPI>), dim3(grid), dim3(64 * WM * WN), smem, ctx->stream, A, W, bias,
+                       res, out, T_dev, N, K, tiles_n);
     LEANN_HIP(hipGetLastError());
     return LEANN_OK;
 }
@@ -486,6 +372,13 @@ int enc_forward(leann_ctx *ctx, const leann_chunks *chunks, const int64_t *ids_d
     int32_t *cu = (int32_t *)ctx->cu.p;
     int64_t *chunk_of = (int64_t *)ctx->enc_ids.p;
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)(d / H));
+    // 256x256 block tiles when every GEMM width allows it (LDS traffic per flop halves); LEANN_GEMM_TILE=128
+    // forces the small tile (tuning aid).
+    static const int tile_pref = [] {
+        const char *v = getenv("LEANN_GEMM_TILE");
+        return v ? atoi(v) : 256;
+    }();
+    const bool big = tile_pref == 256 && d % 256 == 0 && F % 256 == 0;
     static bool att_attr = false;
     if (!att_attr) {
         LEANN_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(attention_kernel),
@@ -516,20 +409,20 @@ int enc_forward(leann_ctx *ctx, const leann_chunks *chunks, const int64_t *ids_d
         };
         for (int l = 0; l < e.layers; ++l) {
             const LayerWeights &w = ctx->layers[l];
-            LEANN_TRY((launch_gemm<128, 128, EPI_BIAS>(ctx, LEANN_PROF_GEMM_QKV, x, w.wqkv, w.bqkv, nullptr, qkv, T_dev,
-                                                       max_rows, 3 * d, d)));
+#define LEANN_GEMM(EPI, KIND, A_, W_, B_, R_, O_, N_, K_)                                                           \
+    LEANN_TRY((big ? launch_gemm<256, 256, EPI>(ctx, KIND, A_, W_, B_, R_, O_, T_dev, max_rows, N_, K_)               \
+                   : launch_gemm<128, 128, EPI>(ctx, KIND, A_, W_, B_, R_, O_, T_dev, max_rows, N_, K_)))
+            LEANN_GEMM(EPI_BIAS, LEANN_PROF_GEMM_QKV, x, w.wqkv, w.bqkv, nullptr, qkv, 3 * d, d);
             {
                 ProfScope prof(ctx, LEANN_PROF_ATTENTION);
                 hipLaunchKernelGGL(attention_kernel, dim3(m, H), dim3(256), ATT_SMEM, ctx->stream, qkv, cu, att, d,
                                    scale_log2e);
             }
-            LEANN_TRY((launch_gemm<128, 128, EPI_BIAS_RES_F32>(ctx, LEANN_PROF_GEMM_O, att, w.wo, w.bo, x, pre, T_dev,
-                                                               max_rows, d, d)));
+            LEANN_GEMM(EPI_BIAS_RES_F32, LEANN_PROF_GEMM_O, att, w.wo, w.bo, x, pre, d, d);
             layer_norm(w.g1, w.be1);
-            LEANN_TRY((launch_gemm<128, 128, EPI_BIAS_GELU>(ctx, LEANN_PROF_GEMM_FFN1, x, w.w1, w.b1, nullptr, hid, T_dev,
-                                                            max_rows, F, d)));
-            LEANN_TRY((launch_gemm<128, 128, EPI_BIAS_RES_F32>(ctx, LEANN_PROF_GEMM_FFN2, hid, w.w2, w.b2, x, pre, T_dev,
-                                                               max_rows, d, F)));
+            LEANN_GEMM(EPI_BIAS_GELU, LEANN_PROF_GEMM_FFN1, x, w.w1, w.b1, nullptr, hid, F, d);
+            LEANN_GEMM(EPI_BIAS_RES_F32, LEANN_PROF_GEMM_FFN2, hid, w.w2, w.b2, x, pre, d, F);
+#undef LEANN_GEMM
             layer_norm(w.g2, w.be2);
         }
         {

@@ -1,0 +1,225 @@
+// bf16 MFMA GEMM with fused epilogues for the encoder's four linear maps (gfx950).
+#pragma once
+#include "common.h"
+
+namespace {
+
+// C[T][N] = A[T][K] * W[N][K]^T (+ epilogue).  bf16 operands, fp32 accumulation in MFMA 32x32x16.
+// Block tile BM x BN, K-slabs of 32, WM x WN waves.  A slab row is four 16-byte chunks; chunk c of row r
+// lives at chunk position c ^ ((r >> 2) & 3), so the row-wise stores and the column-of-rows MFMA operand reads
+// both spread over all LDS banks.
+// Software pipeline (slab s): global loads into one of four register sets at iteration s-5 (memory latency
+// under load is several slabs long), LDS store into a ring of three stages in the middle of iteration s-2,
+// first operand fragments read at the end of iteration s-1, MFMAs at iteration s.  One barrier per slab, and
+// no wave waits on LDS right after it.
+// The 256x256 tile (eight waves of 128x64) halves the bytes fetched from L2 per flop compared with 128x128,
+// which is what bounds the small tile.  Each output element is one fixed-order sum over K: a row's result does
+// not depend on T.
+enum { EPI_BIAS = 0, EPI_BIAS_GELU = 1, EPI_BIAS_RES_F32 = 2 };
+
+// GELU(v) = 0.5 v (1 + erf(v / sqrt 2)) with erf from the five-term rational approximation of Abramowitz & Stegun
+// 7.1.26 (|error| <= 1.5e-7, far below the bf16 rounding of the result): one reciprocal and one exponential.
+__device__ inline float gelu_erf(float v)
+{
+    const float z = fabsf(v) * 0.70710678118654752440f;
+    const float t = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * z);
+    const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
+    const float erf_abs = 1.0f - poly * exp2f(-z * z * 1.4426950408889634f);
+    return 0.5f * v * (1.0f + copysignf(erf_abs, v));
+}
+
+constexpr int GEMM_BK = 32;
+
+template <int BM, int BN, int WM, int WN, int EPI>
+__global__ __launch_bounds__(64 * WM * WN, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_kernel(
+    const bf16_t *__restrict__ A, const bf16_t *__restrict__ W, const float *__restrict__ bias,
+    const bf16_t *__restrict__ res, void *__restrict__ out, const int32_t *__restrict__ T_dev, int N, int K, int tiles_n)
+{
+    constexpr int BK = GEMM_BK;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    bf16_t *As = reinterpret_cast<bf16_t *>(smem);  // [3][BM][BK]
+    bf16_t *Bs = As + 3 * BM * BK;                  // [3][BN][BK]
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WN, wn = wave % WN;
+    constexpr int NT = 64 * WM * WN;                     // threads per block
+    constexpr int TM = BM / WM / 32, TN = BN / WN / 32;  // 32x32 MFMA tiles per wave
+    constexpr int RPP = NT / 4;                          // rows one pass of the block's threads covers
+
+    // Blocks go round-robin to the 8 XCDs; give each XCD a contiguous run of tiles (same A rows, all
+    // column tiles) so that the A slab is reused out of that XCD's L2.
+    const int T = *T_dev;
+    const int n_tiles = ((T + BM - 1) / BM) * tiles_n;
+    const int nb = (n_tiles + 7) & ~7;
+    if ((int)blockIdx.x >= nb) return;
+    const int logical = (blockIdx.x & 7) * (nb >> 3) + (blockIdx.x >> 3);
+    if (logical >= n_tiles) return;
+    const int tile_m = logical / tiles_n, tile_n = logical % tiles_n;
+
+    const bf16_t *Ag = A + (size_t)tile_m * BM * K;
+    const bf16_t *Wg = W + (size_t)tile_n * BN * K;
+    constexpr int ACH = BM / RPP, BCH = BN / RPP;  // 16-byte chunks per thread and K-slab
+    u32x4 ra0[ACH], rb0[BCH], ra1[ACH], rb1[BCH], ra2[ACH], rb2[BCH], ra3[ACH], rb3[BCH];
+    const int lrow = tid >> 2, lc = tid & 3;
+    const bf16_t *ag = Ag + (size_t)lrow * K + lc * 8;
+    const bf16_t *wg = Wg + (size_t)lrow * K + lc * 8;
+    const int soff = lrow * BK + ((lc ^ ((lrow >> 2) & 3)) << 3);  // rows RPP apart share the swizzle term
+
+#define GEMM_GLOAD(RA, RB, k0)                                                                           \
+    _Pragma("unroll") for (int i = 0; i < ACH; ++i)                                                      \
+        RA[i] = *reinterpret_cast<const u32x4 *>(ag + (size_t)(RPP * i) * K + (k0));                      \
+    _Pragma("unroll") for (int i = 0; i < BCH; ++i)                                                      \
+        RB[i] = *reinterpret_cast<const u32x4 *>(wg + (size_t)(RPP * i) * K + (k0));
+#define GEMM_SSTORE(RA, RB, stage)                                                                       \
+    _Pragma("unroll") for (int i = 0; i < ACH; ++i)                                                      \
+        *reinterpret_cast<u32x4 *>(As + (stage) * BM * BK + RPP * BK * i + soff) = RA[i];                 \
+    _Pragma("unroll") for (int i = 0; i < BCH; ++i)                                                      \
+        *reinterpret_cast<u32x4 *>(Bs + (stage) * BN * BK + RPP * BK * i + soff) = RB[i];
+
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
+
+    // operand fragments: lane l reads row (l & 31) of its 32-row block, 16-byte chunk 2*ks + (l >> 5)
+    int a_off[TM][2], b_off[TN][2];
+#pragma unroll
+    for (int mi = 0; mi < TM; ++mi) {
+        const int row = wm * (BM / WM) + mi * 32 + (lane & 31);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) a_off[mi][ks] = row * BK + (((ks * 2 + (lane >> 5)) ^ ((row >> 2) & 3)) << 3);
+    }
+#pragma unroll
+    for (int ni = 0; ni < TN; ++ni) {
+        const int row = wn * (BN / WN) + ni * 32 + (lane & 31);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) b_off[ni][ks] = row * BK + (((ks * 2 + (lane >> 5)) ^ ((row >> 2) & 3)) << 3);
+    }
+
+#define GEMM_FRAGS(AF, BF, stage, ks)                                                                    \
+    _Pragma("unroll") for (int mi = 0; mi < TM; ++mi)                                                    \
+        AF[mi] = *reinterpret_cast<const bf16x8 *>(As + (stage) * BM * BK + a_off[mi][ks]);               \
+    _Pragma("unroll") for (int ni = 0; ni < TN; ++ni)                                                    \
+        BF[ni] = *reinterpret_cast<const bf16x8 *>(Bs + (stage) * BN * BK + b_off[ni][ks]);
+#define GEMM_MFMA(AF, BF)                                                                                \
+    _Pragma("unroll") for (int mi = 0; mi < TM; ++mi)                                                    \
+        _Pragma("unroll") for (int ni = 0; ni < TN; ++ni)                                                \
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(AF[mi], BF[ni], acc[mi][ni], 0, 0, 0);
+    // One iteration: prefetch slab kt+5 into RL, multiply slab kt (its first fragments are already in af0/bf0),
+    // store slab kt+2 (held in RS) into the ring while the MFMAs run, read the first fragments of slab kt+1.
+#define GEMM_ITER(RLA, RLB, RSA, RSB, kt)                                                                \
+    {                                                                                                    \
+        __builtin_amdgcn_sched_barrier(0);                                                               \
+        GEMM_GLOAD(RLA, RLB, min(((kt) + 5) * BK, klast))                                                \
+        GEMM_FRAGS(af1, bf1, st_cur, 1)                                                                  \
+        GEMM_MFMA(af0, bf0)                                                                              \
+        GEMM_SSTORE(RSA, RSB, st_nn)                                                                     \
+        GEMM_FRAGS(af0, bf0, st_nxt, 0)                                                                  \
+        GEMM_MFMA(af1, bf1)                                                                              \
+        GEMM_INTERLEAVE                                                                                  \
+        __builtin_amdgcn_sched_barrier(0);                                                               \
+        __syncthreads();                                                                                 \
+        const int t_ = st_cur;                                                                           \
+        st_cur = st_nxt;                                                                                 \
+        st_nxt = st_nn;                                                                                  \
+        st_nn = t_;                                                                                      \
+    }
+    // Issue order inside an iteration: memory instructions are spread between the MFMAs (a wave issues in order,
+    // so a burst of loads or LDS accesses would hold back its own MFMAs while the memory pipes are busy).
+    // Fragment reads for the second half first, then the global prefetch, the LDS stores, and the next slab's
+    // first fragments once the first half's MFMAs no longer need those registers.
+#define SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0);
+#define GEMM_INTERLEAVE                                                                                  \
+    _Pragma("unroll") for (int i_ = 0; i_ < (TM + TN + 1) / 2; ++i_) { SGB(0x008, 1) SGB(0x100, 2) }     \
+    _Pragma("unroll") for (int i_ = 0; i_ < ACH + BCH; ++i_) { SGB(0x008, 1) SGB(0x020, 1) }             \
+    _Pragma("unroll") for (int i_ = 0; i_ < ACH + BCH; ++i_) { SGB(0x008, 1) SGB(0x200, 1) }             \
+    _Pragma("unroll") for (int i_ = 0; i_ < (TM + TN + 1) / 2; ++i_) { SGB(0x008, 1) SGB(0x100, 2) }     \
+    SGB(0x008, 2 * TM * TN)
+
+    // Loads beyond the last slab re-read the last one (no branch in the loop body keeps the staging arrays in
+    // registers); their LDS stores land in stages nobody reads any more.
+    const int KT = K / BK;  // a multiple of 4: the host checks K % (4 * BK) == 0
+    const int klast = (KT - 1) * BK;
+    bf16x8 af0[TM], bf0[TN], af1[TM], bf1[TN];
+    GEMM_GLOAD(ra0, rb0, 0)
+    GEMM_GLOAD(ra1, rb1, min(BK, klast))
+    GEMM_SSTORE(ra0, rb0, 0)
+    GEMM_SSTORE(ra1, rb1, 1)
+    GEMM_GLOAD(ra1, rb1, min(2 * BK, klast))
+    GEMM_GLOAD(ra2, rb2, min(3 * BK, klast))
+    GEMM_GLOAD(ra3, rb3, min(4 * BK, klast))
+    __syncthreads();
+    GEMM_FRAGS(af0, bf0, 0, 0)
+    int st_cur = 0, st_nxt = 1, st_nn = 2;
+    for (int kt = 0; kt < KT; kt += 4) {
+        GEMM_ITER(ra0, rb0, ra1, rb1, kt)
+        GEMM_ITER(ra1, rb1, ra2, rb2, kt + 1)
+        GEMM_ITER(ra2, rb2, ra3, rb3, kt + 2)
+        GEMM_ITER(ra3, rb3, ra0, rb0, kt + 3)
+    }
+#undef GEMM_GLOAD
+#undef GEMM_SSTORE
+#undef GEMM_FRAGS
+#undef GEMM_MFMA
+#undef GEMM_ITER
+#undef GEMM_INTERLEAVE
+#undef SGB
+
+    // Epilogue.  Accumulator register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32 of its 32x32
+    // tile: a lane owns single elements of many rows.  Each wave transposes 32 rows at a time through its own
+    // slice of LDS so that the global stores are 16 bytes per lane and whole 128-byte row segments per 8 lanes.
+    __syncthreads();  // every wave is done with the operand stages
+    constexpr int WCOLS = BN / WN;
+    constexpr bool RES = EPI == EPI_BIAS_RES_F32;
+    constexpr int EROW = WCOLS * (RES ? 4 : 2) + 16;  // staged row pitch in bytes (the pad spreads the banks)
+    unsigned char *stg = smem + wave * 32 * EROW;
+    const int col0 = tile_n * BN + wn * WCOLS;
+    const int row0 = tile_m * BM + wm * (BM / WM);
+    float bv[TN];
+#pragma unroll
+    for (int ni = 0; ni < TN; ++ni) bv[ni] = bias[col0 + ni * 32 + (lane & 31)];
+#pragma unroll
+    for (int mi = 0; mi < TM; ++mi) {
+#pragma unroll
+        for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int lr = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3), lcol = ni * 32 + (lane & 31);
+                const float v = acc[mi][ni][r] + bv[ni];
+                if (RES)
+                    *reinterpret_cast<float *>(stg + lr * EROW + lcol * 4) = v;
+                else
+                    *reinterpret_cast<bf16_t *>(stg + lr * EROW + lcol * 2) = (bf16_t)(EPI == EPI_BIAS_GELU ? gelu_erf(v) : v);
+            }
+        __builtin_amdgcn_wave_barrier();  // LDS serves a wave's accesses in order: the reads below see the writes
+        if (RES) {
+            constexpr int CPRW = WCOLS / 4;   // 16-byte chunks (4 floats) per staged row
+            constexpr int RPI = 64 / CPRW;    // rows per wave-wide access
+#pragma unroll
+            for (int j = 0; j < 32 / RPI; ++j) {
+                const int lr = j * RPI + lane / CPRW, ch = lane % CPRW;
+                f32x4 v = *reinterpret_cast<const f32x4 *>(stg + lr * EROW + ch * 16);
+                const size_t o = (size_t)(row0 + mi * 32 + lr) * N + col0 + ch * 4;
+                const bf16x4 rv = *reinterpret_cast<const bf16x4 *>(res + o);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[i] += (float)rv[i];
+                *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(out) + o) = v;
+            }
+        } else {
+            constexpr int CPRW = WCOLS / 8;   // 16-byte chunks (8 bf16) per staged row
+            constexpr int RPI = 64 / CPRW;
+#pragma unroll
+            for (int j = 0; j < 32 / RPI; ++j) {
+                const int lr = j * RPI + lane / CPRW, ch = lane % CPRW;
+                const u32x4 v = *reinterpret_cast<const u32x4 *>(stg + lr * EROW + ch * 16);
+                const size_t o = (size_t)(row0 + mi * 32 + lr) * N + col0 + ch * 8;
+                *reinterpret_cast<u32x4 *>(reinterpret_cast<bf16_t *>(out) + o) = v;
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+}
+
+}  // namespace
