@@ -119,6 +119,9 @@ __global__ __launch_bounds__(256) void embed_ln_kernel(const int32_t *__restrict
 }
 
 // ------------------------------------------------------------------ LayerNorm of fp32 rows -> bf16
+// One wave per row; VEC = 4 uses 16-byte loads and 8-byte stores (row length a multiple of 256), VEC = 1 is
+// the general form.  Two-pass statistics on the registers: mean, then the biased variance of the centred values.
+template <int VEC>
 __global__ __launch_bounds__(256) void ln_kernel(const float *__restrict__ in, const float *__restrict__ g,
                                                  const float *__restrict__ b, bf16_t *__restrict__ out,
                                                  const int32_t *__restrict__ T_dev, int d, float eps)
@@ -126,31 +129,50 @@ __global__ __launch_bounds__(256) void ln_kernel(const float *__restrict__ in, c
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= *T_dev) return;
-    const int per = d >> 6;
+    constexpr int MAXP = 16 / VEC;          // rows up to 1024 wide
+    const int per = d / (64 * VEC);
     const float *ir = in + (size_t)row * d;
-    float v[16];
+    float v[MAXP][VEC];
     float s = 0.f;
 #pragma unroll
-    for (int j = 0; j < 16; ++j)
+    for (int j = 0; j < MAXP; ++j)
         if (j < per) {
-            v[j] = ir[j * 64 + lane];
-            s += v[j];
+            if (VEC == 4) {
+                const f32x4 t = *reinterpret_cast<const f32x4 *>(ir + (j * 64 + lane) * 4);
+#pragma unroll
+                for (int i = 0; i < VEC; ++i) v[j][i] = t[i];
+            } else {
+                v[j][0] = ir[j * 64 + lane];
+            }
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) s += v[j][i];
         }
     const float mean = wave_sum(s) / (float)d;
     float q = 0.f;
 #pragma unroll
-    for (int j = 0; j < 16; ++j)
+    for (int j = 0; j < MAXP; ++j)
         if (j < per) {
-            float c = v[j] - mean;
-            q += c * c;
+#pragma unroll
+            for (int i = 0; i < VEC; ++i) {
+                const float c = v[j][i] - mean;
+                q += c * c;
+            }
         }
     const float inv = 1.0f / sqrtf(wave_sum(q) / (float)d + eps);
     bf16_t *orow = out + (size_t)row * d;
 #pragma unroll
-    for (int j = 0; j < 16; ++j)
+    for (int j = 0; j < MAXP; ++j)
         if (j < per) {
-            int c = j * 64 + lane;
-            orow[c] = (bf16_t)((v[j] - mean) * inv * g[c] + b[c]);
+            const int c0 = (j * 64 + lane) * VEC;
+            if (VEC == 4) {
+                const f32x4 gv = *reinterpret_cast<const f32x4 *>(g + c0), bv = *reinterpret_cast<const f32x4 *>(b + c0);
+                bf16x4 o;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) o[i] = (bf16_t)((v[j][i] - mean) * inv * gv[i] + bv[i]);
+                *reinterpret_cast<bf16x4 *>(orow + c0) = o;
+            } else {
+                orow[c0] = (bf16_t)((v[j][0] - mean) * inv * g[c0] + b[c0]);
+            }
         }
 }
 
@@ -160,15 +182,25 @@ __global__ __launch_bounds__(256) void ln_kernel(const float *__restrict__ in, c
 // query column: the softmax reductions run over the lane's own registers plus one exchange with lane^32.
 // P^T (bf16) then feeds O^T = V^T P^T directly from registers: accumulator registers 8u..8u+7 of key tile t
 // are exactly the eight k-slots of one MFMA step when V^T is read with the matching key order.
-constexpr int ATT_VS = 256 + 4;  // V^T row stride (bf16 elements)
-constexpr int ATT_SMEM = (256 * 64 + 64 * ATT_VS) * (int)sizeof(bf16_t);
+// NKT = key tiles (of 32) the block can hold: 4 for sequences up to 128 (half the registers and LDS, twice the
+// blocks per CU), 8 for up to 256.
+template <int NKT>
+struct AttCfg {
+    static constexpr int LP = NKT * 32;           // padded key capacity
+    static constexpr int VS = LP + 4;             // V^T row pitch (bf16): conflict-free 8-byte fragment reads
+    static constexpr int SMEM = (LP * 64 + 64 * VS) * (int)sizeof(bf16_t);
+};
 
-__global__ __launch_bounds__(256) void attention_kernel(const bf16_t *__restrict__ qkv, const int32_t *__restrict__ cu,
-                                                        bf16_t *__restrict__ out, int d, float scale_log2e)
+template <int NKT>
+__global__ __launch_bounds__(256, NKT == 4 ? 3 : 2) void attention_kernel(const bf16_t *__restrict__ qkv,
+                                                                          const int32_t *__restrict__ cu,
+                                                                          bf16_t *__restrict__ out, int d,
+                                                                          float scale_log2e)
 {
+    constexpr int VS = AttCfg<NKT>::VS;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    bf16_t *Ks = reinterpret_cast<bf16_t *>(smem);  // [256][64]
-    bf16_t *Vt = Ks + 256 * 64;                     // [64][ATT_VS]
+    bf16_t *Ks = reinterpret_cast<bf16_t *>(smem);  // [LP][64], 16-byte chunks XOR-swizzled by row
+    bf16_t *Vt = Ks + AttCfg<NKT>::LP * 64;         // [64][VS]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c = blockIdx.x, h = blockIdx.y;
     const int t0 = cu[c], L = cu[c + 1] - t0;
@@ -178,33 +210,50 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t *__restrict
     const size_t ld = (size_t)3 * d;
     const bf16_t *kbase = qkv + (size_t)t0 * ld + d + h * 64;
     const bf16_t *vbase = qkv + (size_t)t0 * ld + 2 * d + h * 64;
+    const int half = lane >> 5, l32 = lane & 31;
 
-    for (int idx = tid; idx < Lp * 8; idx += 256) {
-        const int key = idx >> 3, ch = idx & 7;
-        uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
-        if (key < L) {
-            kv = *reinterpret_cast<const uint4 *>(kbase + (size_t)key * ld + ch * 8);
-            vv = *reinterpret_cast<const uint4 *>(vbase + (size_t)key * ld + ch * 8);
-        }
-        *reinterpret_cast<uint4 *>(Ks + key * 64 + ((ch ^ ((key >> 1) & 7)) << 3)) = kv;
-        const bf16_t *ve = reinterpret_cast<const bf16_t *>(&vv);
+    // the wave's first query block goes to registers while K and V are on their way to LDS
+    bf16x8 qf[4];
+    {
+        const int qload = min(wave * 32 + l32, L - 1);
+        const bf16_t *qp = qkv + (size_t)(t0 + qload) * ld + h * 64;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) Vt[(ch * 8 + i) * ATT_VS + key] = ve[i];
+        for (int s = 0; s < 4; ++s) qf[s] = *reinterpret_cast<const bf16x8 *>(qp + s * 16 + half * 8);
+    }
+    // K rows as they are; V transposed, two keys per 4-byte LDS store.  Keys >= L are zero.
+    for (int idx = tid; idx < Lp * 4; idx += 256) {
+        const int kp = idx >> 3, ch = idx & 7, key = kp * 2;
+        u32x4 k0 = {0, 0, 0, 0}, k1 = {0, 0, 0, 0}, v0 = {0, 0, 0, 0}, v1 = {0, 0, 0, 0};
+        if (key < L) {
+            k0 = *reinterpret_cast<const u32x4 *>(kbase + (size_t)key * ld + ch * 8);
+            v0 = *reinterpret_cast<const u32x4 *>(vbase + (size_t)key * ld + ch * 8);
+        }
+        if (key + 1 < L) {
+            k1 = *reinterpret_cast<const u32x4 *>(kbase + (size_t)(key + 1) * ld + ch * 8);
+            v1 = *reinterpret_cast<const u32x4 *>(vbase + (size_t)(key + 1) * ld + ch * 8);
+        }
+        *reinterpret_cast<u32x4 *>(Ks + key * 64 + ((ch ^ ((key >> 1) & 7)) << 3)) = k0;
+        *reinterpret_cast<u32x4 *>(Ks + (key + 1) * 64 + ((ch ^ (((key + 1) >> 1) & 7)) << 3)) = k1;
+        uint32_t *vt32 = reinterpret_cast<uint32_t *>(Vt);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const uint32_t a = (v0[i >> 1] >> (16 * (i & 1))) & 0xffffu, b = (v1[i >> 1] >> (16 * (i & 1))) & 0xffffu;
+            vt32[((ch * 8 + i) * VS + key) >> 1] = a | (b << 16);
+        }
     }
     __syncthreads();
 
-    const int half = lane >> 5, l32 = lane & 31;
     for (int qb = wave; qb < nkt; qb += 4) {
         const int qrow = qb * 32 + l32;
-        const int qload = min(qrow, L - 1);
-        const bf16_t *qp = qkv + (size_t)(t0 + qload) * ld + h * 64;
-        bf16x8 qf[4];
+        if (qb != wave) {
+            const int qload = min(qrow, L - 1);
+            const bf16_t *qp = qkv + (size_t)(t0 + qload) * ld + h * 64;
 #pragma unroll
-        for (int s = 0; s < 4; ++s) qf[s] = *reinterpret_cast<const bf16x8 *>(qp + s * 16 + half * 8);
-
-        f32x16 sc[8];
+            for (int s = 0; s < 4; ++s) qf[s] = *reinterpret_cast<const bf16x8 *>(qp + s * 16 + half * 8);
+        }
+        f32x16 sc[NKT];
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
+        for (int t = 0; t < NKT; ++t) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) sc[t][r] = 0.f;
             if (t < nkt) {
@@ -216,23 +265,24 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t *__restrict
                 }
             }
         }
-        // lane owns query column l32 and keys 32t + 8(r/4) + 4*half + r%4
+        // lane owns query column l32 and keys 32t + 8(r/4) + 4*half + r%4; only the last tile can hold keys >= L
         float mx = -INFINITY;
 #pragma unroll
-        for (int t = 0; t < 8; ++t)
+        for (int t = 0; t < NKT; ++t)
             if (t < nkt) {
+                if (t == nkt - 1) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int key = t * 32 + 8 * (r >> 2) + 4 * half + (r & 3);
-                    if (key >= L) sc[t][r] = -INFINITY;
-                    mx = fmaxf(mx, sc[t][r]);
+                    for (int r = 0; r < 16; ++r)
+                        if (t * 32 + 8 * (r >> 2) + 4 * half + (r & 3) >= L) sc[t][r] = -INFINITY;
                 }
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sc[t][r]);
             }
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
         const float moff = mx * scale_log2e;
         float den = 0.f;
 #pragma unroll
-        for (int t = 0; t < 8; ++t)
+        for (int t = 0; t < NKT; ++t)
             if (t < nkt) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
@@ -249,7 +299,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t *__restrict
 #pragma unroll
             for (int r = 0; r < 16; ++r) oacc[dt][r] = 0.f;
 #pragma unroll
-        for (int t = 0; t < 8; ++t)
+        for (int t = 0; t < NKT; ++t)
             if (t < nkt) {
 #pragma unroll
                 for (int u = 0; u < 2; ++u) {
@@ -259,7 +309,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const bf16_t *__restrict
                     const int k0 = t * 32 + u * 16 + 4 * half;  // slots 0..3 -> keys k0..k0+3, slots 4..7 -> k0+8..k0+11
 #pragma unroll
                     for (int dt = 0; dt < 2; ++dt) {
-                        const bf16_t *vr = Vt + (dt * 32 + l32) * ATT_VS + k0;
+                        const bf16_t *vr = Vt + (dt * 32 + l32) * VS + k0;
                         bf16x4 lo = *reinterpret_cast<const bf16x4 *>(vr);
                         bf16x4 hi = *reinterpret_cast<const bf16x4 *>(vr + 8);
                         bf16x8 vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
@@ -381,8 +431,8 @@ int enc_forward(leann_ctx *ctx, const leann_chunks *chunks, const int64_t *ids_d
     const bool big = tile_pref == 256 && d % 256 == 0 && F % 256 == 0;
     static bool att_attr = false;
     if (!att_attr) {
-        LEANN_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(attention_kernel),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, ATT_SMEM));
+        LEANN_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(attention_kernel<8>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, AttCfg<8>::SMEM));
         att_attr = true;
     }
 
@@ -405,7 +455,10 @@ int enc_forward(leann_ctx *ctx, const leann_chunks *chunks, const int64_t *ids_d
         const int ln_grid = (max_rows + 3) / 4;
         auto layer_norm = [&](const float *g, const float *b) {
             ProfScope prof(ctx, LEANN_PROF_LAYERNORM);
-            hipLaunchKernelGGL(ln_kernel, dim3(ln_grid), dim3(256), 0, ctx->stream, pre, g, b, x, T_dev, d, e.ln_eps);
+            if (d % 256 == 0)
+                hipLaunchKernelGGL(ln_kernel<4>, dim3(ln_grid), dim3(256), 0, ctx->stream, pre, g, b, x, T_dev, d, e.ln_eps);
+            else
+                hipLaunchKernelGGL(ln_kernel<1>, dim3(ln_grid), dim3(256), 0, ctx->stream, pre, g, b, x, T_dev, d, e.ln_eps);
         };
         for (int l = 0; l < e.layers; ++l) {
             const LayerWeights &w = ctx->layers[l];
@@ -415,8 +468,12 @@ int enc_forward(leann_ctx *ctx, const leann_chunks *chunks, const int64_t *ids_d
             LEANN_GEMM(EPI_BIAS, LEANN_PROF_GEMM_QKV, x, w.wqkv, w.bqkv, nullptr, qkv, 3 * d, d);
             {
                 ProfScope prof(ctx, LEANN_PROF_ATTENTION);
-                hipLaunchKernelGGL(attention_kernel, dim3(m, H), dim3(256), ATT_SMEM, ctx->stream, qkv, cu, att, d,
-                                   scale_log2e);
+                if (seq <= 128)
+                    hipLaunchKernelGGL(attention_kernel<4>, dim3(m, H), dim3(256), AttCfg<4>::SMEM, ctx->stream, qkv, cu,
+                                       att, d, scale_log2e);
+                else
+                    hipLaunchKernelGGL(attention_kernel<8>, dim3(m, H), dim3(256), AttCfg<8>::SMEM, ctx->stream, qkv, cu,
+                                       att, d, scale_log2e);
             }
             LEANN_GEMM(EPI_BIAS_RES_F32, LEANN_PROF_GEMM_O, att, w.wo, w.bo, x, pre, d, d);
             layer_norm(w.g1, w.be1);
