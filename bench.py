@@ -22,6 +22,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak (published)
+# HBM-side bytes per valid token per GEMM launch (average of the QKV, O, FFN1, FFN2 launches), from the rocprofv3
+# FETCH_SIZE / WRITE_SIZE runs summarised in profiles/encoder_seq256_hbm_traffic.md (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0
+# after calibration against a 1 GiB copy); the algorithmic minimum is 7.7 KB.
+GEMM_TRAFFIC_BYTES_PER_TOKEN = 12.9e3
 
 
 def log(*a):
@@ -237,7 +241,10 @@ def main():
                            "kernel_ms_per_step": all_ms / args.steps},
         "roofline": {"bound": "mfma", "kernel": "gemm_kernel (QKV, O, FFN1, FFN2 launches)", "achieved": gemm_tflops,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": gemm_tflops / PEAK_BF16_TFLOPS,
-                     "traffic": None, "avg_launch_ms": gemm_ms / gemm_launches if gemm_launches else None,
+                     "traffic": GEMM_TRAFFIC_BYTES_PER_TOKEN * prof["tokens"] * cfg["layers"] * 4 / gemm_launches
+                     if gemm_launches else None, "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE/WRITE_SIZE, "
+                     "calibrated, measured on the seq-256 encoder pass and scaled by tokens per launch)",
+                     "avg_launch_ms": gemm_ms / gemm_launches if gemm_launches else None,
                      "launches": gemm_launches,
                      "flops_per_launch": prof["tokens"] * gemm_flops_per_token(cfg) / gemm_launches
                      if gemm_launches else None},
