@@ -135,6 +135,11 @@ int leann_create(leann_ctx **out, const leann_encoder_desc *desc, const void *we
     ctx->desc = e;
     ctx->device = device;
     ctx->stream = (hipStream_t)hip_stream;
+    {
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, device) == hipSuccess && prop.multiProcessorCount >= 8)
+            ctx->num_cus = prop.multiProcessorCount;
+    }
     const size_t d = e.hidden, F = e.ffn, L = e.layers;
     const size_t n_emb = ((size_t)e.vocab + e.max_pos + 1) * d;
     size_t bf_bytes = up256(e.vocab * d * 2) + up256(e.max_pos * d * 2) + up256(d * 2) +

@@ -49,6 +49,7 @@ struct DevBuf {
 struct leann_ctx {
     leann_encoder_desc desc;
     int device = 0;
+    int num_cus = 256;
     hipStream_t stream = nullptr;
     // weights
     DevBuf w_bf16, w_f32;

@@ -7,6 +7,8 @@
 // so grids are sized for the worst case and blocks beyond T leave at once.
 #include <stdlib.h>
 
+#include <algorithm>
+
 #include "common.h"
 #include "gemm.h"
 
@@ -386,7 +388,9 @@ int launch_gemm(leann_ctx *ctx, int prof_kind, const bf16_t *A, const bf16_t *W,
     }
     const int tiles_n = N / BN;
     const int tiles = ((max_rows + BM - 1) / BM) * tiles_n;
-    const int grid = (tiles + 7) & ~7;
+    // persistent blocks: one per CU slot (a multiple of 8), fewer when there are fewer tiles
+    const int slots = ctx->num_cus * ((BM * BN <= 128 * 128) ? 2 : 1);
+    const int grid = std::max(8, std::min(slots, (tiles + 7) & ~7) & ~7);
     ProfScope prof(ctx, prof_kind);
     hipLaunchKernelGGL((gemm_kernel<BM, BN, WM, WN, EPI>), dim3(grid), dim3(64 * WM * WN), smem, ctx->stream, A, W, bias,
                        res, out, T_dev, N, K, tiles_n);

@@ -45,24 +45,18 @@ __global__ __launch_bounds__(64 * WM * WN, (BM * BN <= 128 * 128) ? 2 : 1) void 
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;  // 32x32 MFMA tiles per wave
     constexpr int RPP = NT / 4;                          // rows one pass of the block's threads covers
 
-    // Blocks go round-robin to the 8 XCDs; give each XCD a contiguous run of tiles (same A rows, all
-    // column tiles) so that the A slab is reused out of that XCD's L2 (measured: 2.3x fewer bytes fetched by
-    // the QKV GEMM than with the plain block order).
+    // Persistent blocks: the grid is one block per CU slot and every block walks over tiles, so the output stores
+    // of one tile drain while the next tile's operands are already being fetched (with one block per CU nothing
+    // else would hide them).  Blocks go round-robin to the 8 XCDs: block b sits on XCD b % 8.  At step j the
+    // blocks of one XCD take a contiguous run of tiles (same A rows, all column tiles), so the A slab is reused out
+    // of that XCD's L2 (measured: 2.3x fewer bytes fetched by the QKV GEMM than with the plain tile order).
     const int T = *T_dev;
     const int n_tiles = ((T + BM - 1) / BM) * tiles_n;
-    const int nb = (n_tiles + 7) & ~7;
-    if ((int)blockIdx.x >= nb) return;
-    const int logical = (blockIdx.x & 7) * (nb >> 3) + (blockIdx.x >> 3);
-    if (logical >= n_tiles) return;
-    const int tile_m = logical / tiles_n, tile_n = logical % tiles_n;
-
-    const bf16_t *Ag = A + (size_t)tile_m * BM * K;
-    const bf16_t *Wg = W + (size_t)tile_n * BN * K;
+    const int per_xcd = (n_tiles + 7) >> 3;
+    const int blocks_per_xcd = gridDim.x >> 3;  // the host launches a multiple of 8 blocks
     constexpr int ACH = BM / RPP, BCH = BN / RPP;  // 16-byte chunks per thread and K-slab
     u32x4 ra0[ACH], rb0[BCH], ra1[ACH], rb1[BCH], ra2[ACH], rb2[BCH], ra3[ACH], rb3[BCH];
     const int lrow = tid >> 2, lc = tid & 3;
-    const bf16_t *ag = Ag + (size_t)lrow * K + lc * 8;
-    const bf16_t *wg = Wg + (size_t)lrow * K + lc * 8;
     const int soff = lrow * BK + ((lc ^ ((lrow >> 2) & 3)) << 3);  // rows RPP apart share the swizzle term
 
 #define GEMM_GLOAD(RA, RB, k0)                                                                           \
@@ -76,13 +70,6 @@ __global__ __launch_bounds__(64 * WM * WN, (BM * BN <= 128 * 128) ? 2 : 1) void 
     _Pragma("unroll") for (int i = 0; i < BCH; ++i)                                                      \
         *reinterpret_cast<u32x4 *>(Bs + (stage) * BN * BK + RPP * BK * i + soff) = RB[i];
 
-    f32x16 acc[TM][TN];
-#pragma unroll
-    for (int mi = 0; mi < TM; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < TN; ++ni)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
 
     // operand fragments: lane l reads row (l & 31) of its 32-row block, 16-byte chunk 2*ks + (l >> 5)
     int a_off[TM][2], b_off[TN][2];
@@ -127,17 +114,40 @@ __global__ __launch_bounds__(64 * WM * WN, (BM * BN <= 128 * 128) ? 2 : 1) void 
         st_nxt = st_nn;                                                                                  \
         st_nn = t_;                                                                                      \
     }
-    // Issue order inside an iteration: memory instructions are spread between the MFMAs (a wave issues in order,
-    // so a burst of loads or LDS accesses would hold back its own MFMAs while the memory pipes are busy).
-    // Fragment reads for the second half first, then the global prefetch, the LDS stores, and the next slab's
-    // first fragments once the first half's MFMAs no longer need those registers.
+    // Issue order inside an iteration.  A wave issues in order, and all waves of the block run the same schedule
+    // at the same time: a burst of global loads (16 cycles each in the address unit) or LDS stores fills the
+    // memory pipes' queues and holds back the MFMAs behind it.  So the memory instructions are spread evenly
+    // between the MFMAs: fragment reads for the second half first, one global load and one LDS store every four
+    // MFMAs, the next slab's first fragments once the first half's MFMAs no longer need those registers.
 #define SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0);
 #define GEMM_INTERLEAVE                                                                                  \
-    _Pragma("unroll") for (int i_ = 0; i_ < (TM + TN + 1) / 2; ++i_) { SGB(0x008, 1) SGB(0x100, 2) }     \
-    _Pragma("unroll") for (int i_ = 0; i_ < ACH + BCH; ++i_) { SGB(0x008, 1) SGB(0x020, 1) }             \
-    _Pragma("unroll") for (int i_ = 0; i_ < ACH + BCH; ++i_) { SGB(0x008, 1) SGB(0x200, 1) }             \
-    _Pragma("unroll") for (int i_ = 0; i_ < (TM + TN + 1) / 2; ++i_) { SGB(0x008, 1) SGB(0x100, 2) }     \
-    SGB(0x008, 2 * TM * TN)
+    if constexpr (TM * TN == 8 && TM + TN == 6 && ACH + BCH == 4) {                                      \
+        SGB(0x008, 1) SGB(0x100, 2) SGB(0x008, 1) SGB(0x020, 1) SGB(0x008, 1) SGB(0x100, 2) SGB(0x008, 1) SGB(0x200, 1) \
+        SGB(0x008, 1) SGB(0x100, 2) SGB(0x008, 1) SGB(0x020, 1) SGB(0x008, 1) SGB(0x200, 1) SGB(0x008, 1)               \
+        SGB(0x008, 1) SGB(0x100, 2) SGB(0x008, 1) SGB(0x020, 1) SGB(0x008, 1) SGB(0x100, 2) SGB(0x008, 1) SGB(0x200, 1) \
+        SGB(0x008, 1) SGB(0x100, 2) SGB(0x008, 1) SGB(0x020, 1) SGB(0x008, 1) SGB(0x200, 1) SGB(0x008, 1)               \
+    } else {                                                                                             \
+        _Pragma("unroll") for (int i_ = 0; i_ < (TM + TN + 1) / 2; ++i_) { SGB(0x008, 1) SGB(0x100, 2) } \
+        _Pragma("unroll") for (int i_ = 0; i_ < ACH + BCH; ++i_) { SGB(0x008, 1) SGB(0x020, 1) }         \
+        _Pragma("unroll") for (int i_ = 0; i_ < ACH + BCH; ++i_) { SGB(0x008, 1) SGB(0x200, 1) }         \
+        _Pragma("unroll") for (int i_ = 0; i_ < (TM + TN + 1) / 2; ++i_) { SGB(0x008, 1) SGB(0x100, 2) } \
+        SGB(0x008, 2 * TM * TN)                                                                          \
+    }
+
+  for (int step = 0; step * blocks_per_xcd < per_xcd; ++step) {
+    const int in_xcd = step * blocks_per_xcd + (int)(blockIdx.x >> 3);
+    const int logical = (int)(blockIdx.x & 7) * per_xcd + in_xcd;
+    if (in_xcd >= per_xcd || logical >= n_tiles) break;  // uniform for the block
+    const int tile_m = logical / tiles_n, tile_n = logical % tiles_n;
+    const bf16_t *ag = A + ((size_t)tile_m * BM + lrow) * K + lc * 8;
+    const bf16_t *wg = W + ((size_t)tile_n * BN + lrow) * K + lc * 8;
+    f32x16 acc[TM][TN];
+#pragma unroll
+    for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+        for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
 
     // Loads beyond the last slab re-read the last one (no branch in the loop body keeps the staging arrays in
     // registers); their LDS stores land in stages nobody reads any more.
@@ -160,13 +170,6 @@ __global__ __launch_bounds__(64 * WM * WN, (BM * BN <= 128 * 128) ? 2 : 1) void 
         GEMM_ITER(ra2, rb2, ra3, rb3, kt + 2)
         GEMM_ITER(ra3, rb3, ra0, rb0, kt + 3)
     }
-#undef GEMM_GLOAD
-#undef GEMM_SSTORE
-#undef GEMM_FRAGS
-#undef GEMM_MFMA
-#undef GEMM_ITER
-#undef GEMM_INTERLEAVE
-#undef SGB
 
     // Epilogue.  Accumulator register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32 of its 32x32
     // tile: a lane owns single elements of many rows.  Each wave transposes 32 rows at a time through its own
@@ -221,6 +224,15 @@ __global__ __launch_bounds__(64 * WM * WN, (BM * BN <= 128 * 128) ? 2 : 1) void 
         }
         __builtin_amdgcn_wave_barrier();
     }
+    __syncthreads();  // the staging slices are operand stages again for the next tile
+  }
+#undef GEMM_GLOAD
+#undef GEMM_SSTORE
+#undef GEMM_FRAGS
+#undef GEMM_MFMA
+#undef GEMM_ITER
+#undef GEMM_INTERLEAVE
+#undef SGB
 }
 
 }  // namespace
