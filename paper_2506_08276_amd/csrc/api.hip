@@ -205,7 +205,7 @@ void leann_destroy(leann_ctx *ctx)
     (void)hipStreamSynchronize(ctx->stream);
     DevBuf *bufs[] = {&ctx->w_bf16, &ctx->w_f32, &ctx->x, &ctx->qkv, &ctx->att, &ctx->pre, &ctx->hid, &ctx->cu,
                       &ctx->len, &ctx->meta, &ctx->enc_ids, &ctx->s_state, &ctx->s_emb, &ctx->s_lut, &ctx->s_seen,
-                      &ctx->s_misc};
+                      &ctx->s_misc, &ctx->s_owner};
     for (DevBuf *b : bufs) b->release();
     ctx->prof_tokens.release();
     for (auto &sp : ctx->prof_spans) {

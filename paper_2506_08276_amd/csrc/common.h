@@ -62,7 +62,7 @@ struct leann_ctx {
     // encoder workspace
     DevBuf x, qkv, att, pre, hid, cu, len, meta, enc_ids;
     // search workspace
-    DevBuf s_state, s_emb, s_lut, s_seen, s_misc;
+    DevBuf s_state, s_emb, s_lut, s_seen, s_misc, s_owner;
     // optional per-kernel timing (leann_profile_begin / leann_profile_end)
     bool prof_on = false;
     DevBuf prof_tokens;  // device int64: valid tokens sent through the encoder while profiling

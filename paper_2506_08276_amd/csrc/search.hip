@@ -29,6 +29,7 @@ struct SearchState {
     uint32_t *pend;       // [G][pcap]
     int32_t *n_pend;      // [G]
     int32_t *src;         // [G][pcap]  >= 0: row of the encoder output, < 0: -(cache row + 1)
+    int32_t *owner;       // [N] smallest pending entry (q * pcap + j) that asked for the chunk this round, else INT_MAX
     int32_t *done;        // [G]
     int32_t *enc_off;     // [G + 1]
     int64_t *enc_ids;     // [G * pcap]
@@ -235,8 +236,24 @@ __global__ __launch_bounds__(64) void traverse_kernel(SearchState s, const uint6
     }
 }
 
-// Pack the pending lists: encoder input list (entries not served by the cache), per-entry source rows,
-// and the round's totals.  One block of 1024 threads.
+// Chunks that several queries ask for in the same round are encoded once: the pending entry with the smallest
+// index (q * pcap + j) owns the chunk, the others read the owner's row.  The encoder's output for a chunk does
+// not depend on its batch, so every query still sees exactly the scores it would compute alone.
+constexpr int NO_OWNER = 0x7f7f7f7f;  // the fill byte 0x7f makes hipMemsetAsync usable
+
+__global__ __launch_bounds__(64) void claim_kernel(SearchState s, const int32_t *__restrict__ slot_of)
+{
+    const int q = blockIdx.x;
+    const int np = s.n_pend[q];
+    for (int j = threadIdx.x; j < np; j += 64) {
+        const uint32_t c = s.pend[(size_t)q * s.pcap + j];
+        if (slot_of && slot_of[c] >= 0) continue;
+        atomicMin(&s.owner[c], q * s.pcap + j);
+    }
+}
+
+// Pack the round: encoder input list (one entry per owned chunk, in entry order), source rows of the owners and
+// of the entries served by the stored-embedding table, and the round's totals.  One block of 1024 threads.
 __global__ __launch_bounds__(1024) void collect_kernel(SearchState s, int g, const int32_t *__restrict__ slot_of)
 {
     __shared__ int part[1024];
@@ -247,11 +264,7 @@ __global__ __launch_bounds__(1024) void collect_kernel(SearchState s, int g, con
     for (int q = beg; q < end; ++q) {
         const int np = s.n_pend[q];
         pending += np;
-        if (slot_of) {
-            for (int j = 0; j < np; ++j) need += slot_of[s.pend[(size_t)q * s.pcap + j]] < 0;
-        } else {
-            need += np;
-        }
+        for (int j = 0; j < np; ++j) need += s.owner[s.pend[(size_t)q * s.pcap + j]] == q * s.pcap + j;
     }
     part[tid] = need;
     __syncthreads();
@@ -266,13 +279,14 @@ __global__ __launch_bounds__(1024) void collect_kernel(SearchState s, int g, con
         s.enc_off[q] = run;
         const int np = s.n_pend[q];
         for (int j = 0; j < np; ++j) {
-            const uint32_t c = s.pend[(size_t)q * s.pcap + j];
+            const int e = q * s.pcap + j;
+            const uint32_t c = s.pend[e];
             const int slot = slot_of ? slot_of[c] : -1;
-            if (slot < 0) {
+            if (slot >= 0) {
+                s.src[e] = -(slot + 1);
+            } else if (s.owner[c] == e) {
                 s.enc_ids[run] = c;
-                s.src[(size_t)q * s.pcap + j] = run++;
-            } else {
-                s.src[(size_t)q * s.pcap + j] = -(slot + 1);
+                s.src[e] = run++;
             }
         }
     }
@@ -281,6 +295,20 @@ __global__ __launch_bounds__(1024) void collect_kernel(SearchState s, int g, con
         s.counters[CTR_NENC] = part[1023];
     }
     if (pending) atomicAdd((unsigned long long *)&s.counters[CTR_PENDING], (unsigned long long)pending);
+}
+
+// Entries that do not own their chunk take the owner's row.
+__global__ __launch_bounds__(64) void resolve_kernel(SearchState s, const int32_t *__restrict__ slot_of)
+{
+    const int q = blockIdx.x;
+    const int np = s.n_pend[q];
+    for (int j = threadIdx.x; j < np; j += 64) {
+        const int e = q * s.pcap + j;
+        const uint32_t c = s.pend[e];
+        if (slot_of && slot_of[c] >= 0) continue;
+        const int o = s.owner[c];
+        if (o != e) s.src[e] = s.src[o];
+    }
 }
 
 // Exact scores of the pending chunks and try-insert into EQ, in pending order.  One wavefront per query.
@@ -347,6 +375,7 @@ __global__ __launch_bounds__(64) void score_insert_kernel(SearchState s, const f
         s.eq_id[(size_t)q * s.ef + i] = eqi[i];
         s.eq_vis[(size_t)q * s.ef + i] = eqv[i];
     }
+    for (int j = lane; j < np; j += 64) s.owner[s.pend[(size_t)q * s.pcap + j]] = NO_OWNER;  // free for the next round
     if (lane == 0) {
         s.eq_n[q] = n_eq;
         s.n_pend[q] = 0;
@@ -449,6 +478,8 @@ int search_run(leann_ctx *ctx, const float *queries_dev, int64_t nq, const leann
     LEANN_TRY(ctx->s_seen.reserve((size_t)G * words * 4));
     LEANN_TRY(ctx->s_lut.reserve((size_t)G * m_sub * KSUB * sizeof(float)));
     LEANN_TRY(ctx->s_emb.reserve((size_t)G * pcap * d * sizeof(float)));
+    LEANN_TRY(ctx->s_owner.reserve((size_t)n * sizeof(int32_t)));
+    LEANN_HIP(hipMemsetAsync(ctx->s_owner.p, 0x7f, (size_t)n * sizeof(int32_t), st));
     char *base = (char *)ctx->s_state.p;
     SearchState s;
     s.eq_score = (float *)(base + o_eqs);
@@ -463,6 +494,7 @@ int search_run(leann_ctx *ctx, const float *queries_dev, int64_t nq, const leann
     s.n_pend = (int32_t *)(base + o_np);
     s.src = (int32_t *)(base + o_src);
     s.done = (int32_t *)(base + o_done);
+    s.owner = (int32_t *)ctx->s_owner.p;
     s.enc_off = (int32_t *)(base + o_eoff);
     s.enc_ids = (int64_t *)(base + o_eids);
     s.counters = counters;
@@ -512,7 +544,10 @@ int search_run(leann_ctx *ctx, const float *queries_dev, int64_t nq, const leann
             LEANN_HIP(hipMemsetAsync(&counters[CTR_PENDING], 0, 2 * sizeof(long long), st));
             {
                 ProfScope prof(ctx, LEANN_PROF_COLLECT);
-                hipLaunchKernelGGL(collect_kernel, dim3(1), dim3(1024), 0, st, s, g, cache ? cache->slot_of : nullptr);
+                const int32_t *slot_of = cache ? cache->slot_of : nullptr;
+                hipLaunchKernelGGL(claim_kernel, dim3(g), dim3(64), 0, st, s, slot_of);
+                hipLaunchKernelGGL(collect_kernel, dim3(1), dim3(1024), 0, st, s, g, slot_of);
+                hipLaunchKernelGGL(resolve_kernel, dim3(g), dim3(64), 0, st, s, slot_of);
             }
             LEANN_HIP(hipMemcpyAsync(h_ctr, counters, sizeof(h_ctr), hipMemcpyDeviceToHost, st));
             LEANN_TRY(mark());

@@ -108,7 +108,7 @@ def full_path_case(L, orc, w, ctx, pq, graph, t, l, q, ef, k, alpha, batch, labe
     nq = len(runs)
     print(f"{label}: {decided}/{nq * k} ranks decided (gap > 1e-3, stable under bf16 storage) and all equal; {agree}/{nq * k} ranks and "
           f"{full}/{nq} whole results equal to the fp32 oracle's; stats {st}")
-    assert st["recomputed_chunks"] > 0 and st["encoded_chunks"] == st["recomputed_chunks"]
+    assert 0 < st["encoded_chunks"] <= st["recomputed_chunks"]  # chunks shared by queries in a round are encoded once
     return decided
 
 
