@@ -31,7 +31,7 @@ __device__ inline float gelu_erf(float v)
 constexpr int GEMM_BK = 32;
 
 template <int BM, int BN, int WM, int WN, int EPI>
-__global__ __launch_bounds__(64 * WM * WN, (BM * BN <= 128 * 128) ? 2 : 1) void gemm_kernel(
+__global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4) ? 2 : 1) void gemm_kernel(
     const bf16_t *__restrict__ A, const bf16_t *__restrict__ W, const float *__restrict__ bias,
     const bf16_t *__restrict__ res, void *__restrict__ out, const int32_t *__restrict__ T_dev, int N, int K, int tiles_n)
 {

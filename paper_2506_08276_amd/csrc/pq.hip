@@ -117,30 +117,66 @@ __global__ __launch_bounds__(256) void lut_kernel(const float *__restrict__ quer
     lut[((size_t)q * m_sub + m) * KSUB + c] = -s;
 }
 
-// out[q][j] = sum_m lut[q][m][codes[cand[q][j]][m]], m ascending.  grid (nq, ceil(nc / 1024)), 256 threads;
-// the query's table sits in LDS.
+// out[q][j] = sum_m lut[q][m][codes[cand[q][j]][m]], m ascending.  grid (nq, ceil(nc / 2048)), 256 threads;
+// the query's table sits in LDS.  A thread owns up to 8 candidates: all their ids, then all their code rows
+// are requested before the first lookup, so that the random row gathers overlap instead of queueing up.
+constexpr int ADC_PER_BLOCK = 2048, ADC_PER_THREAD = ADC_PER_BLOCK / 256;
+
 __global__ __launch_bounds__(256) void adc_kernel(const float *__restrict__ lut, const uint8_t *__restrict__ codes,
                                                   int64_t n, int m_sub, const uint32_t *__restrict__ cand, int nc,
                                                   float *__restrict__ out, int *__restrict__ err)
 {
     extern __shared__ float tab[];  // [m_sub][256]
     const int q = blockIdx.x;
+    const int j0 = blockIdx.y * ADC_PER_BLOCK + threadIdx.x;
+    uint32_t v[ADC_PER_THREAD];
+#pragma unroll
+    for (int i = 0; i < ADC_PER_THREAD; ++i) {
+        const int j = j0 + i * 256;
+        v[i] = j < nc ? cand[(size_t)q * nc + j] : 0xffffffffu;
+    }
     const float4 *src = reinterpret_cast<const float4 *>(lut + (size_t)q * m_sub * KSUB);
     for (int i = threadIdx.x; i < m_sub * KSUB / 4; i += 256) reinterpret_cast<float4 *>(tab)[i] = src[i];
+    if (m_sub == 32) {  // 32-byte rows: both halves of every row in flight before any lookup
+        u32x4 c0[ADC_PER_THREAD], c1[ADC_PER_THREAD];
+#pragma unroll
+        for (int i = 0; i < ADC_PER_THREAD; ++i) {
+            const uint8_t *code = codes + (size_t)(v[i] < n ? v[i] : 0) * 32;
+            c0[i] = *reinterpret_cast<const u32x4 *>(code);
+            c1[i] = *reinterpret_cast<const u32x4 *>(code + 16);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < ADC_PER_THREAD; ++i) {
+            const int j = j0 + i * 256;
+            if (j >= nc) continue;
+            float s = 0.f;
+#pragma unroll
+            for (int m = 0; m < 16; ++m) s += tab[m * KSUB + ((c0[i][m >> 2] >> (8 * (m & 3))) & 255u)];
+#pragma unroll
+            for (int m = 0; m < 16; ++m) s += tab[(16 + m) * KSUB + ((c1[i][m >> 2] >> (8 * (m & 3))) & 255u)];
+            if (v[i] >= n) {
+                atomicOr(err, 1);
+                s = -INFINITY;
+            }
+            out[(size_t)q * nc + j] = s;
+        }
+        return;
+    }
     __syncthreads();
-    const int j0 = blockIdx.y * 1024;
-    for (int j = j0 + threadIdx.x; j < min(nc, j0 + 1024); j += 256) {
-        const uint32_t v = cand[(size_t)q * nc + j];
+#pragma unroll
+    for (int i = 0; i < ADC_PER_THREAD; ++i) {
+        const int j = j0 + i * 256;
+        if (j >= nc) continue;
         float s = -INFINITY;
-        if (v < n) {
-            const uint8_t *code = codes + (size_t)v * m_sub;
+        if (v[i] < n) {
+            const uint8_t *code = codes + (size_t)v[i] * m_sub;
             s = 0.f;
             if ((m_sub & 15) == 0) {
                 for (int m0 = 0; m0 < m_sub; m0 += 16) {
-                    const uint4 w = *reinterpret_cast<const uint4 *>(code + m0);
-                    const uint32_t ww[4] = {w.x, w.y, w.z, w.w};
+                    const u32x4 w = *reinterpret_cast<const u32x4 *>(code + m0);
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) s += tab[(m0 + i) * KSUB + ((ww[i >> 2] >> (8 * (i & 3))) & 255u)];
+                    for (int m = 0; m < 16; ++m) s += tab[(m0 + m) * KSUB + ((w[m >> 2] >> (8 * (m & 3))) & 255u)];
                 }
             } else {
                 for (int m = 0; m < m_sub; ++m) s += tab[m * KSUB + code[m]];
@@ -387,7 +423,8 @@ int leann_adc(leann_ctx *ctx, const float *queries_dev, int64_t nq, const leann_
     }
     {
         ProfScope prof(ctx, LEANN_PROF_ADC);
-        hipLaunchKernelGGL(adc_kernel, dim3((unsigned)nq, (nc + 1023) / 1024), dim3(256), smem, ctx->stream,
+        hipLaunchKernelGGL(adc_kernel, dim3((unsigned)nq, (nc + ADC_PER_BLOCK - 1) / ADC_PER_BLOCK), dim3(256), smem,
+                           ctx->stream,
                            (const float *)ctx->s_lut.p, pq->codes, pq->n, pq->m_sub, cand_ids_dev, nc, out_dev, err);
     }
     LEANN_HIP(hipGetLastError());

@@ -1,0 +1,86 @@
+"""GPU checks in the launch configuration bench.py times (BERT-base-shape encoder, seq 128, latent-position
+corpus, navigable fixture, 32-byte PQ), at a size the test can afford: sampled outputs against the oracle and
+properties that hold at any size."""
+import argparse
+
+import numpy as np
+import pytest
+
+import leann_inputs as li
+from gpu_util import say
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def world():
+    import torch
+    import bench
+    import paper_2506_08276_amd as L
+    L.load_library()
+    args = argparse.Namespace(n=12000, nq=96, seq=128, pq_iters=6)
+    say("bench world N=12000 nq=96 (BERT-base shape, seq 128)")
+    w = bench.build_world(args, L, torch)
+    w["L"], w["torch"], w["args"] = L, torch, args
+    yield w
+    L.leann_pq_free(w["pq"])
+    L.leann_destroy(w["ctx"])
+
+
+def search(w, queries, ef=64, k=3, alpha=0.1, batch=64, cache=None):
+    return w["L"].leann_search(w["ctx"], queries, w["graph"], w["pq"], w["t"], w["l"], ef, k, alpha, batch, cache=cache)
+
+
+def test_sampled_embeddings_and_adc_against_oracle(orc, world):
+    w, L, torch = world, world["L"], world["torch"]
+    cfg = w["cfg"]
+    ids = np.array([0, 77, 5000, 11999], np.int64)
+    say("sampled embeddings vs oracle", ids)
+    wts = li.encoder_weights(cfg, w["seed"], bf16_exact=True)
+    want = orc.embed(orc.desc(**cfg), wts, w["tokens"], w["lengths"], ids=ids)
+    got = w["emb"][torch.from_numpy(ids).cuda()].cpu().numpy()
+    assert np.abs(got - want).max() <= 2e-2
+    say("sampled ADC vs oracle on the exported table")
+    cb, codes = L.leann_pq_export(w["ctx"], w["pq"])
+    rng = np.random.default_rng(0)
+    cand = rng.integers(0, w["args"].n, size=(8, 50)).astype(np.uint32)
+    q = w["queries"][:8].contiguous()
+    adc = L.leann_adc(w["ctx"], q, w["pq"], torch.from_numpy(cand.view(np.int32)).cuda()).cpu().numpy()
+    qh = q.cpu().numpy()
+    for i in range(8):
+        ref, _ = orc.adc(orc.lut(qh[i], cb), codes, cand[i])
+        assert np.all(np.abs(adc[i] - ref) <= 1e-4 * np.abs(ref))
+
+
+def test_search_properties_at_bench_configuration(world):
+    w, L, torch = world, world["L"], world["torch"]
+    nq, n = w["args"].nq, w["args"].n
+    say("search, bench parameters ef=64 alpha=0.1 batch=64")
+    ids, scores, st = search(w, w["queries"])
+    assert ids.shape == (nq, 3) and bool(((ids >= 0) & (ids < n)).all())
+    assert all(len(set(r.tolist())) == 3 for r in ids)
+    assert bool((scores[:, :-1] >= scores[:, 1:]).all())
+    # exact scores are inner products with the embeddings leann_embed returns for the same chunks
+    ref = torch.einsum("qkd,qd->qk", w["emb"][ids], w["queries"])
+    assert float((scores - ref).abs().max()) <= 1e-5
+    # recall against the exact top-3 over the stored embeddings (the bench's ground truth)
+    recall = (ids.unsqueeze(2) == w["gt"].unsqueeze(1)).any(2).sum().item() / w["gt"].numel()
+    print(f"recall@3 at ef=64: {recall:.3f}; {st['recomputed_chunks'] / nq:.0f} recomputed and "
+          f"{st['encoded_chunks'] / nq:.0f} encoded chunks per query, {st['rounds']} rounds")
+    assert recall >= 0.85
+    assert 0 < st["encoded_chunks"] <= st["recomputed_chunks"] and st["hops"] >= nq
+    # a query's answer does not depend on the rest of the call
+    say("split call")
+    a, sa, _ = search(w, w["queries"][:40].contiguous())
+    b, sb, _ = search(w, w["queries"][40:].contiguous())
+    assert torch.equal(torch.cat([a, b]), ids) and torch.equal(torch.cat([sa, sb]), scores)
+    # recomputation equals reading the same embeddings from the stored-embedding table
+    say("stored-embedding table covering every node")
+    cache = (torch.arange(n, dtype=torch.int32, device="cuda"), w["emb"])
+    c_ids, c_scores, c_st = search(w, w["queries"], cache=cache)
+    assert torch.equal(c_ids, ids) and torch.equal(c_scores, scores)
+    assert c_st["encoded_chunks"] == 0 and c_st["recomputed_chunks"] == st["recomputed_chunks"]
+    # larger queue: recall does not drop, more work
+    ids2, _, st2 = search(w, w["queries"], ef=160)
+    recall2 = (ids2.unsqueeze(2) == w["gt"].unsqueeze(1)).any(2).sum().item() / w["gt"].numel()
+    assert recall2 >= recall - 0.02 and st2["recomputed_chunks"] > st["recomputed_chunks"]
