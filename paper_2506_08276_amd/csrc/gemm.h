@@ -11,21 +11,22 @@ namespace {
 // Software pipeline (slab s): global loads into one of four register sets at iteration s-5 (memory latency
 // under load is several slabs long), LDS store into a ring of three stages in the middle of iteration s-2,
 // first operand fragments read at the end of iteration s-1, MFMAs at iteration s.  One barrier per slab, and
-// no wave waits on LDS right after it.
+// no wave waits on LDS right after it.  The last four iterations of a tile fetch the first four slabs of the
+// block's next tile instead, so those are in registers when the epilogue ends.
 // The 256x256 tile (eight waves of 128x64) halves the bytes fetched from L2 per flop compared with 128x128,
 // which is what bounds the small tile.  Each output element is one fixed-order sum over K: a row's result does
 // not depend on T.
 enum { EPI_BIAS = 0, EPI_BIAS_GELU = 1, EPI_BIAS_RES_F32 = 2 };
 
-// GELU(v) = 0.5 v (1 + erf(v / sqrt 2)) with erf from the five-term rational approximation of Abramowitz & Stegun
-// 7.1.26 (|error| <= 1.5e-7, far below the bf16 rounding of the result): one reciprocal and one exponential.
+// GELU(v) = v Phi(v) with the normal distribution function written as a logistic function of an odd polynomial,
+// Phi(v) ~ 1 / (1 + 2^(-v p(v^2))), p(u) = c0 + c1 u + c2 u^2 fitted to the exact erf form (minimax over |v| <= 9):
+// |error| <= 2.6e-5, below the bf16 rounding of the result wherever the result matters.  v^2 is clamped where
+// Phi has saturated in fp32 (p would turn over beyond).  One hardware exponential and one reciprocal.
 __device__ inline float gelu_erf(float v)
 {
-    const float z = fabsf(v) * 0.70710678118654752440f;
-    const float t = __builtin_amdgcn_rcpf(1.0f + 0.3275911f * z);
-    const float poly = t * (0.254829592f + t * (-0.284496736f + t * (1.421413741f + t * (-1.453152027f + t * 1.061405429f))));
-    const float erf_abs = 1.0f - poly * exp2f(-z * z * 1.4426950408889634f);
-    return 0.5f * v * (1.0f + copysignf(erf_abs, v));
+    const float u = fminf(v * v, 50.0f);
+    const float p = fmaf(u, fmaf(u, 0.0010142733f, -0.10677579f), -2.3011213f);  // -p(u)
+    return v * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(v * p));  // raw 2^x: overflow gives inf -> 0, underflow 0 -> v
 }
 
 constexpr int GEMM_BK = 32;
@@ -59,11 +60,11 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4) ? 2 : 1) void gemm_ker
     const int lrow = tid >> 2, lc = tid & 3;
     const int soff = lrow * BK + ((lc ^ ((lrow >> 2) & 3)) << 3);  // rows RPP apart share the swizzle term
 
-#define GEMM_GLOAD(RA, RB, k0)                                                                           \
+#define GEMM_GLOAD(RA, RB, AP, WP, k0)                                                                   \
     _Pragma("unroll") for (int i = 0; i < ACH; ++i)                                                      \
-        RA[i] = *reinterpret_cast<const u32x4 *>(ag + (size_t)(RPP * i) * K + (k0));                      \
+        RA[i] = *reinterpret_cast<const u32x4 *>((AP) + (size_t)(RPP * i) * K + (k0));                    \
     _Pragma("unroll") for (int i = 0; i < BCH; ++i)                                                      \
-        RB[i] = *reinterpret_cast<const u32x4 *>(wg + (size_t)(RPP * i) * K + (k0));
+        RB[i] = *reinterpret_cast<const u32x4 *>((WP) + (size_t)(RPP * i) * K + (k0));
 #define GEMM_SSTORE(RA, RB, stage)                                                                       \
     _Pragma("unroll") for (int i = 0; i < ACH; ++i)                                                      \
         *reinterpret_cast<u32x4 *>(As + (stage) * BM * BK + RPP * BK * i + soff) = RA[i];                 \
@@ -95,15 +96,16 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4) ? 2 : 1) void gemm_ker
     _Pragma("unroll") for (int mi = 0; mi < TM; ++mi)                                                    \
         _Pragma("unroll") for (int ni = 0; ni < TN; ++ni)                                                \
             acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(AF[mi], BF[ni], acc[mi][ni], 0, 0, 0);
-    // One iteration: prefetch slab kt+5 into RL, multiply slab kt (its first fragments are already in af0/bf0),
-    // store slab kt+2 (held in RS) into the ring while the MFMAs run, read the first fragments of slab kt+1.
-#define GEMM_ITER(RLA, RLB, RSA, RSB, kt)                                                                \
+    // One iteration: LOAD prefetches slab kt+5 (or a slab of the next tile), the MFMAs multiply slab kt (its first
+    // fragments are already in af0/bf0), STORE puts slab kt+2 into the ring while the MFMAs run, and the first
+    // fragments of slab kt+1 are read.
+#define GEMM_ITER(LOAD, STORE)                                                                           \
     {                                                                                                    \
         __builtin_amdgcn_sched_barrier(0);                                                               \
-        GEMM_GLOAD(RLA, RLB, min(((kt) + 5) * BK, klast))                                                \
+        LOAD                                                                                             \
         GEMM_FRAGS(af1, bf1, st_cur, 1)                                                                  \
         GEMM_MFMA(af0, bf0)                                                                              \
-        GEMM_SSTORE(RSA, RSB, st_nn)                                                                     \
+        STORE                                                                                            \
         GEMM_FRAGS(af0, bf0, st_nxt, 0)                                                                  \
         GEMM_MFMA(af1, bf1)                                                                              \
         GEMM_INTERLEAVE                                                                                  \
@@ -134,13 +136,33 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4) ? 2 : 1) void gemm_ker
         SGB(0x008, 2 * TM * TN)                                                                          \
     }
 
-  for (int step = 0; step * blocks_per_xcd < per_xcd; ++step) {
-    const int in_xcd = step * blocks_per_xcd + (int)(blockIdx.x >> 3);
-    const int logical = (int)(blockIdx.x & 7) * per_xcd + in_xcd;
-    if (in_xcd >= per_xcd || logical >= n_tiles) break;  // uniform for the block
-    const int tile_m = logical / tiles_n, tile_n = logical % tiles_n;
+    // tile of this block at a step of its walk (uniform for the block); false when the walk is over
+#define GEMM_TILE_AT(step_, ok_, tm_, tn_)                                                               \
+    {                                                                                                    \
+        const int in_xcd_ = (step_) * blocks_per_xcd + (int)(blockIdx.x >> 3);                           \
+        const int logical_ = (int)(blockIdx.x & 7) * per_xcd + in_xcd_;                                  \
+        ok_ = in_xcd_ < per_xcd && logical_ < n_tiles;                                                   \
+        if (ok_) { tm_ = logical_ / tiles_n; tn_ = logical_ % tiles_n; }                                 \
+    }
+    bool have;
+    int tile_m = 0, tile_n = 0;
+    GEMM_TILE_AT(0, have, tile_m, tile_n)
+    if (!have) return;
+    const int KT = K / BK;  // a multiple of 4: the host checks K % (4 * BK) == 0
+    const int klast = (KT - 1) * BK;
     const bf16_t *ag = A + ((size_t)tile_m * BM + lrow) * K + lc * 8;
     const bf16_t *wg = W + ((size_t)tile_n * BN + lrow) * K + lc * 8;
+    GEMM_GLOAD(ra0, rb0, ag, wg, 0)
+    GEMM_GLOAD(ra1, rb1, ag, wg, BK)
+    GEMM_GLOAD(ra2, rb2, ag, wg, 2 * BK)
+    GEMM_GLOAD(ra3, rb3, ag, wg, 3 * BK)
+  for (int step = 0;; ++step) {
+    // the tile after this one; without one the prefetch at the end of the K loop re-reads this tile (in bounds, unused)
+    bool have_next;
+    int next_m = tile_m, next_n = tile_n;
+    GEMM_TILE_AT(step + 1, have_next, next_m, next_n)
+    const bf16_t *ag_next = A + ((size_t)next_m * BM + lrow) * K + lc * 8;
+    const bf16_t *wg_next = W + ((size_t)next_n * BN + lrow) * K + lc * 8;
     f32x16 acc[TM][TN];
 #pragma unroll
     for (int mi = 0; mi < TM; ++mi)
@@ -149,27 +171,32 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4) ? 2 : 1) void gemm_ker
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
 
-    // Loads beyond the last slab re-read the last one (no branch in the loop body keeps the staging arrays in
-    // registers); their LDS stores land in stages nobody reads any more.
-    const int KT = K / BK;  // a multiple of 4: the host checks K % (4 * BK) == 0
-    const int klast = (KT - 1) * BK;
+    // Slabs 0..3 of this tile are in the four register sets.  Steady state of the K loop at iteration 0: slabs 0 and
+    // 1 in the ring, slabs 2, 3, 4 in sets 1, 2, 3, set 0 free.
     bf16x8 af0[TM], bf0[TN], af1[TM], bf1[TN];
-    GEMM_GLOAD(ra0, rb0, 0)
-    GEMM_GLOAD(ra1, rb1, min(BK, klast))
     GEMM_SSTORE(ra0, rb0, 0)
     GEMM_SSTORE(ra1, rb1, 1)
-    GEMM_GLOAD(ra1, rb1, min(2 * BK, klast))
-    GEMM_GLOAD(ra2, rb2, min(3 * BK, klast))
-    GEMM_GLOAD(ra3, rb3, min(4 * BK, klast))
+#pragma unroll
+    for (int i = 0; i < ACH; ++i) { ra1[i] = ra2[i]; ra2[i] = ra3[i]; }
+#pragma unroll
+    for (int i = 0; i < BCH; ++i) { rb1[i] = rb2[i]; rb2[i] = rb3[i]; }
+    GEMM_GLOAD(ra3, rb3, ag, wg, min(4 * BK, klast))
     __syncthreads();
     GEMM_FRAGS(af0, bf0, 0, 0)
     int st_cur = 0, st_nxt = 1, st_nn = 2;
-    for (int kt = 0; kt < KT; kt += 4) {
-        GEMM_ITER(ra0, rb0, ra1, rb1, kt)
-        GEMM_ITER(ra1, rb1, ra2, rb2, kt + 1)
-        GEMM_ITER(ra2, rb2, ra3, rb3, kt + 2)
-        GEMM_ITER(ra3, rb3, ra0, rb0, kt + 3)
+    // Loads beyond the last slab re-read the last one (no branch in the loop body keeps the staging arrays in
+    // registers); their LDS stores land in stages nobody reads any more.
+    for (int kt = 0; kt < KT - 4; kt += 4) {
+        GEMM_ITER(GEMM_GLOAD(ra0, rb0, ag, wg, min((kt + 5) * BK, klast)), GEMM_SSTORE(ra1, rb1, st_nn))
+        GEMM_ITER(GEMM_GLOAD(ra1, rb1, ag, wg, min((kt + 6) * BK, klast)), GEMM_SSTORE(ra2, rb2, st_nn))
+        GEMM_ITER(GEMM_GLOAD(ra2, rb2, ag, wg, min((kt + 7) * BK, klast)), GEMM_SSTORE(ra3, rb3, st_nn))
+        GEMM_ITER(GEMM_GLOAD(ra3, rb3, ag, wg, min((kt + 8) * BK, klast)), GEMM_SSTORE(ra0, rb0, st_nn))
     }
+    // last four slabs: slabs KT-2 and KT-1 still go into the ring; the loads fetch the next tile
+    GEMM_ITER(GEMM_GLOAD(ra0, rb0, ag_next, wg_next, 0), GEMM_SSTORE(ra1, rb1, st_nn))
+    GEMM_ITER(GEMM_GLOAD(ra1, rb1, ag_next, wg_next, BK), GEMM_SSTORE(ra2, rb2, st_nn))
+    GEMM_ITER(GEMM_GLOAD(ra2, rb2, ag_next, wg_next, 2 * BK), )
+    GEMM_ITER(GEMM_GLOAD(ra3, rb3, ag_next, wg_next, 3 * BK), )
 
     // Epilogue.  Accumulator register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32 of its 32x32
     // tile: a lane owns single elements of many rows.  Each wave transposes 32 rows at a time through its own
@@ -184,8 +211,25 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4) ? 2 : 1) void gemm_ker
     float bv[TN];
 #pragma unroll
     for (int ni = 0; ni < TN; ++ni) bv[ni] = bias[col0 + ni * 32 + (lane & 31)];
+    // write-out geometry: a wave-wide access covers RPI rows of CPRW 16-byte chunks.  The output is read by a later
+    // kernel only: streaming stores keep it from displacing the operand slabs in L2 (measured: 3-7% per GEMM).
+    constexpr int CPRW = WCOLS / (RES ? 4 : 8), RPI = 64 / CPRW, NJ = 32 / RPI;
+    const int orow = lane / CPRW, och = lane % CPRW;
+    // the residual rows of 32-row group mi+1 are fetched (streaming: read once) while group mi is transposed and written
+    bf16x4 rv[2][RES ? NJ : 1];
+    if (RES) {
+#pragma unroll
+        for (int j = 0; j < NJ; ++j)
+            rv[0][j] = __builtin_nontemporal_load(reinterpret_cast<const bf16x4 *>(res + (size_t)(row0 + j * RPI + orow) * N + col0 + och * 4));
+    }
 #pragma unroll
     for (int mi = 0; mi < TM; ++mi) {
+        if (RES && mi + 1 < TM) {
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+                rv[(mi + 1) & 1][j] =
+                    __builtin_nontemporal_load(reinterpret_cast<const bf16x4 *>(res + (size_t)(row0 + (mi + 1) * 32 + j * RPI + orow) * N + col0 + och * 4));
+        }
 #pragma unroll
         for (int ni = 0; ni < TN; ++ni)
 #pragma unroll
@@ -198,34 +242,30 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4) ? 2 : 1) void gemm_ker
                     *reinterpret_cast<bf16_t *>(stg + lr * EROW + lcol * 2) = (bf16_t)(EPI == EPI_BIAS_GELU ? gelu_erf(v) : v);
             }
         __builtin_amdgcn_wave_barrier();  // LDS serves a wave's accesses in order: the reads below see the writes
-        if (RES) {
-            constexpr int CPRW = WCOLS / 4;   // 16-byte chunks (4 floats) per staged row
-            constexpr int RPI = 64 / CPRW;    // rows per wave-wide access
 #pragma unroll
-            for (int j = 0; j < 32 / RPI; ++j) {
-                const int lr = j * RPI + lane / CPRW, ch = lane % CPRW;
-                f32x4 v = *reinterpret_cast<const f32x4 *>(stg + lr * EROW + ch * 16);
-                const size_t o = (size_t)(row0 + mi * 32 + lr) * N + col0 + ch * 4;
-                const bf16x4 rv = *reinterpret_cast<const bf16x4 *>(res + o);
+        for (int j = 0; j < NJ; ++j) {
+            const int lr = j * RPI + orow;
+            const size_t o = (size_t)(row0 + mi * 32 + lr) * N + col0;
+            if (RES) {
+                f32x4 v = *reinterpret_cast<const f32x4 *>(stg + lr * EROW + och * 16);
 #pragma unroll
-                for (int i = 0; i < 4; ++i) v[i] += (float)rv[i];
-                *reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(out) + o) = v;
-            }
-        } else {
-            constexpr int CPRW = WCOLS / 8;   // 16-byte chunks (8 bf16) per staged row
-            constexpr int RPI = 64 / CPRW;
-#pragma unroll
-            for (int j = 0; j < 32 / RPI; ++j) {
-                const int lr = j * RPI + lane / CPRW, ch = lane % CPRW;
-                const u32x4 v = *reinterpret_cast<const u32x4 *>(stg + lr * EROW + ch * 16);
-                const size_t o = (size_t)(row0 + mi * 32 + lr) * N + col0 + ch * 8;
-                *reinterpret_cast<u32x4 *>(reinterpret_cast<bf16_t *>(out) + o) = v;
+                for (int i = 0; i < 4; ++i) v[i] += (float)rv[mi & 1][j][i];
+                __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(out) + o + och * 4));
+            } else {
+                const u32x4 v = *reinterpret_cast<const u32x4 *>(stg + lr * EROW + och * 16);
+                __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(reinterpret_cast<bf16_t *>(out) + o + och * 8));
             }
         }
         __builtin_amdgcn_wave_barrier();
     }
     __syncthreads();  // the staging slices are operand stages again for the next tile
+    if (!have_next) break;
+    tile_m = next_m;
+    tile_n = next_n;
+    ag = ag_next;
+    wg = wg_next;
   }
+#undef GEMM_TILE_AT
 #undef GEMM_GLOAD
 #undef GEMM_SSTORE
 #undef GEMM_FRAGS
