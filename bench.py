@@ -53,6 +53,8 @@ def build_world(args, L, torch):
     t0 = time.time()
     w = li.encoder_weights(cfg, seed, bf16_exact=True)
     ctx = L.leann_create(cfg, torch.from_numpy(w).to(dev).to(torch.bfloat16))
+    if getattr(args, "max_tokens", 0):
+        L.leann_set_limits(ctx, args.max_tokens, 0)
     del w
     space = li.make_latent_space(cfg["vocab"], seed + 1)
     corpus = li.latent_corpus(space, args.n, args.seq, args.seq // 4, args.seq, seed + 2)
@@ -155,6 +157,7 @@ def main():
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--pq-iters", type=int, default=10)
     ap.add_argument("--target-recall", type=float, default=0.90)
+    ap.add_argument("--max-tokens", type=int, default=0, help="padded tokens per encoder pass (0 = library default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-encoder-bench", action="store_true")
     args = ap.parse_args()

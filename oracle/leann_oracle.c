@@ -177,7 +177,8 @@ static float gelu_erf(float v) { return 0.5f * v * (1.0f + erff(v * 0.7071067811
 
 /* One chunk.  prec = 0: plain fp32.  prec = 1: every tensor a bf16 pipeline
  * would keep in memory (post-LN activations, QKV, softmax weights entering
- * the value product, attention output, GELU output) is rounded to bf16;
+ * the value product, attention output, GELU output, the output of the two
+ * projections that feed a residual add) is rounded to bf16;
  * sums, softmax and LN statistics stay fp32.  Weights are expected to be
  * rounded by the caller in that mode (orc_embed does it). */
 static int encode_chunk(const orc_encoder_desc *e, const emb_w *ew, const layer_w *lw, const int32_t *ids,
@@ -234,7 +235,7 @@ static int encode_chunk(const orc_encoder_desc *e, const emb_w *ew, const layer_
             }
         linear(att, L, d, w->wo, w->bo, d, y);
         for (int t = 0; t < L; ++t) {
-            for (int i = 0; i < d; ++i) x[(int64_t)t * d + i] += y[(int64_t)t * d + i];
+            for (int i = 0; i < d; ++i) x[(int64_t)t * d + i] += prec ? bf16_rne(y[(int64_t)t * d + i]) : y[(int64_t)t * d + i];
             layer_norm(x + (int64_t)t * d, d, w->g1, w->b1n, e->ln_eps, prec);
         }
         linear(x, L, d, w->w1, w->b1, F, hid);
@@ -244,7 +245,7 @@ static int encode_chunk(const orc_encoder_desc *e, const emb_w *ew, const layer_
         }
         linear(hid, L, F, w->w2, w->b2, d, y);
         for (int t = 0; t < L; ++t) {
-            for (int i = 0; i < d; ++i) x[(int64_t)t * d + i] += y[(int64_t)t * d + i];
+            for (int i = 0; i < d; ++i) x[(int64_t)t * d + i] += prec ? bf16_rne(y[(int64_t)t * d + i]) : y[(int64_t)t * d + i];
             layer_norm(x + (int64_t)t * d, d, w->g2, w->b2n, e->ln_eps, prec);
         }
     }

@@ -57,7 +57,7 @@ struct leann_ctx {
     const float *emb_g = nullptr, *emb_b = nullptr;
     std::vector<LayerWeights> layers;
     // limits
-    int64_t max_tokens = 262144;
+    int64_t max_tokens = 1048576;  // padded tokens per encoder pass (workspaces: about 17 KB per token at BERT-base width)
     int32_t aq_capacity = 0;  // 0 = derive from ef and graph
     // encoder workspace
     DevBuf x, qkv, att, pre, hid, cu, len, meta, enc_ids;

@@ -120,61 +120,59 @@ __global__ __launch_bounds__(256) void embed_ln_kernel(const int32_t *__restrict
         }
 }
 
-// ------------------------------------------------------------------ LayerNorm of fp32 rows -> bf16
-// One wave per row; VEC = 4 uses 16-byte loads and 8-byte stores (row length a multiple of 256), VEC = 1 is
-// the general form.  Two-pass statistics on the registers: mean, then the biased variance of the centred values.
-template <int VEC>
-__global__ __launch_bounds__(256) void ln_kernel(const float *__restrict__ in, const float *__restrict__ g,
-                                                 const float *__restrict__ b, bf16_t *__restrict__ out,
+// ------------------------------------------------------------------ residual add + LayerNorm, in place
+// x[row] = LN(x[row] + delta[row]): delta is a sublayer's output (bf16, written by the O / FFN2 GEMM), the sum, the
+// statistics and the normalisation are fp32.  One wave per row, the whole row in registers before anything is
+// written.  A lane owns 16-byte pieces (8 elements) j*64 + lane of the row (row length a multiple of 8, at most
+// 1024).  Two-pass statistics on the registers: mean, then the biased variance of the centred values.
+__global__ __launch_bounds__(256) void ln_kernel(const bf16_t *__restrict__ delta, const float *__restrict__ g,
+                                                 const float *__restrict__ b, bf16_t *__restrict__ x,
                                                  const int32_t *__restrict__ T_dev, int d, float eps)
 {
     const int lane = threadIdx.x & 63;
     const int row = blockIdx.x * 4 + (threadIdx.x >> 6);
     if (row >= *T_dev) return;
-    constexpr int MAXP = 16 / VEC;          // rows up to 1024 wide
-    const int per = d / (64 * VEC);
-    const float *ir = in + (size_t)row * d;
-    float v[MAXP][VEC];
+    const int pieces = d >> 3;
+    const bf16_t *dr = delta + (size_t)row * d;
+    bf16_t *xr = x + (size_t)row * d;
+    float v[2][8];
     float s = 0.f;
 #pragma unroll
-    for (int j = 0; j < MAXP; ++j)
-        if (j < per) {
-            if (VEC == 4) {
-                const f32x4 t = *reinterpret_cast<const f32x4 *>(ir + (j * 64 + lane) * 4);
+    for (int j = 0; j < 2; ++j)
+        if (j * 64 + lane < pieces) {
+            const bf16x8 t = __builtin_nontemporal_load(reinterpret_cast<const bf16x8 *>(dr + (j * 64 + lane) * 8));
+            const bf16x8 r = *reinterpret_cast<const bf16x8 *>(xr + (j * 64 + lane) * 8);
 #pragma unroll
-                for (int i = 0; i < VEC; ++i) v[j][i] = t[i];
-            } else {
-                v[j][0] = ir[j * 64 + lane];
+            for (int i = 0; i < 8; ++i) {
+                v[j][i] = (float)r[i] + (float)t[i];
+                s += v[j][i];
             }
-#pragma unroll
-            for (int i = 0; i < VEC; ++i) s += v[j][i];
         }
     const float mean = wave_sum(s) / (float)d;
     float q = 0.f;
 #pragma unroll
-    for (int j = 0; j < MAXP; ++j)
-        if (j < per) {
+    for (int j = 0; j < 2; ++j)
+        if (j * 64 + lane < pieces) {
 #pragma unroll
-            for (int i = 0; i < VEC; ++i) {
+            for (int i = 0; i < 8; ++i) {
                 const float c = v[j][i] - mean;
                 q += c * c;
             }
         }
     const float inv = 1.0f / sqrtf(wave_sum(q) / (float)d + eps);
-    bf16_t *orow = out + (size_t)row * d;
 #pragma unroll
-    for (int j = 0; j < MAXP; ++j)
-        if (j < per) {
-            const int c0 = (j * 64 + lane) * VEC;
-            if (VEC == 4) {
-                const f32x4 gv = *reinterpret_cast<const f32x4 *>(g + c0), bv = *reinterpret_cast<const f32x4 *>(b + c0);
-                bf16x4 o;
+    for (int j = 0; j < 2; ++j)
+        if (j * 64 + lane < pieces) {
+            const int c0 = (j * 64 + lane) * 8;
+            const f32x4 g0 = *reinterpret_cast<const f32x4 *>(g + c0), g1 = *reinterpret_cast<const f32x4 *>(g + c0 + 4);
+            const f32x4 b0 = *reinterpret_cast<const f32x4 *>(b + c0), b1 = *reinterpret_cast<const f32x4 *>(b + c0 + 4);
+            bf16x8 o;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) o[i] = (bf16_t)((v[j][i] - mean) * inv * gv[i] + bv[i]);
-                *reinterpret_cast<bf16x4 *>(orow + c0) = o;
-            } else {
-                orow[c0] = (bf16_t)((v[j][0] - mean) * inv * g[c0] + b[c0]);
+            for (int i = 0; i < 4; ++i) {
+                o[i] = (bf16_t)((v[j][i] - mean) * inv * g0[i] + b0[i]);
+                o[i + 4] = (bf16_t)((v[j][i + 4] - mean) * inv * g1[i] + b1[i]);
             }
+            *reinterpret_cast<bf16x8 *>(xr + c0) = o;
         }
 }
 
@@ -371,8 +369,8 @@ __global__ __launch_bounds__(256) void pool_kernel(const bf16_t *__restrict__ x,
 }
 
 template <int BM, int BN, int EPI>
-int launch_gemm(leann_ctx *ctx, int prof_kind, const bf16_t *A, const bf16_t *W, const float *bias, const bf16_t *res,
-                void *out, const int32_t *T_dev, int max_rows, int N, int K)
+int launch_gemm(leann_ctx *ctx, int prof_kind, const bf16_t *A, const bf16_t *W, const float *bias, bf16_t *out,
+                const int32_t *T_dev, int max_rows, int N, int K)
 {
     static bool attr_done = false;
     constexpr int WM = 2, WN = (BM * BN <= 128 * 128) ? 2 : 4;
@@ -393,7 +391,7 @@ int launch_gemm(leann_ctx *ctx, int prof_kind, const bf16_t *A, const bf16_t *W,
     const int grid = std::max(8, std::min(slots, (tiles + 7) & ~7) & ~7);
     ProfScope prof(ctx, prof_kind);
     hipLaunchKernelGGL((gemm_kernel<BM, BN, WM, WN, EPI>), dim3(grid), dim3(64 * WM * WN), smem, ctx->stream, A, W, bias,
-                       res, out, T_dev, N, K, tiles_n);
+                       out, T_dev, N, K, tiles_n);
     LEANN_HIP(hipGetLastError());
     return LEANN_OK;
 }
@@ -417,12 +415,12 @@ int enc_forward(leann_ctx *ctx, const leann_chunks *chunks, const int64_t *ids_d
     LEANN_TRY(ctx->x.reserve(rows * d * sizeof(bf16_t)));
     LEANN_TRY(ctx->qkv.reserve(rows * 3 * d * sizeof(bf16_t)));
     LEANN_TRY(ctx->att.reserve(rows * d * sizeof(bf16_t)));
-    LEANN_TRY(ctx->pre.reserve(rows * d * sizeof(float)));
+    LEANN_TRY(ctx->pre.reserve(rows * d * sizeof(bf16_t)));
     LEANN_TRY(ctx->hid.reserve(rows * F * sizeof(bf16_t)));
     LEANN_TRY(ctx->cu.reserve((size_t)(per_pass + 1) * sizeof(int32_t)));
     LEANN_TRY(ctx->enc_ids.reserve((size_t)per_pass * sizeof(int64_t)));
     bf16_t *x = (bf16_t *)ctx->x.p, *qkv = (bf16_t *)ctx->qkv.p, *att = (bf16_t *)ctx->att.p, *hid = (bf16_t *)ctx->hid.p;
-    float *pre = (float *)ctx->pre.p;
+    bf16_t *delta = (bf16_t *)ctx->pre.p;  // sublayer output waiting for its residual add + LayerNorm
     int32_t *cu = (int32_t *)ctx->cu.p;
     int64_t *chunk_of = (int64_t *)ctx->enc_ids.p;
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)(d / H));
@@ -459,17 +457,14 @@ int enc_forward(leann_ctx *ctx, const leann_chunks *chunks, const int64_t *ids_d
         const int ln_grid = (max_rows + 3) / 4;
         auto layer_norm = [&](const float *g, const float *b) {
             ProfScope prof(ctx, LEANN_PROF_LAYERNORM);
-            if (d % 256 == 0)
-                hipLaunchKernelGGL(ln_kernel<4>, dim3(ln_grid), dim3(256), 0, ctx->stream, pre, g, b, x, T_dev, d, e.ln_eps);
-            else
-                hipLaunchKernelGGL(ln_kernel<1>, dim3(ln_grid), dim3(256), 0, ctx->stream, pre, g, b, x, T_dev, d, e.ln_eps);
+            hipLaunchKernelGGL(ln_kernel, dim3(ln_grid), dim3(256), 0, ctx->stream, delta, g, b, x, T_dev, d, e.ln_eps);
         };
         for (int l = 0; l < e.layers; ++l) {
             const LayerWeights &w = ctx->layers[l];
-#define LEANN_GEMM(EPI, KIND, A_, W_, B_, R_, O_, N_, K_)                                                           \
-    LEANN_TRY((big ? launch_gemm<256, 256, EPI>(ctx, KIND, A_, W_, B_, R_, O_, T_dev, max_rows, N_, K_)               \
-                   : launch_gemm<128, 128, EPI>(ctx, KIND, A_, W_, B_, R_, O_, T_dev, max_rows, N_, K_)))
-            LEANN_GEMM(EPI_BIAS, LEANN_PROF_GEMM_QKV, x, w.wqkv, w.bqkv, nullptr, qkv, 3 * d, d);
+#define LEANN_GEMM(EPI, KIND, A_, W_, B_, O_, N_, K_)                                                               \
+    LEANN_TRY((big ? launch_gemm<256, 256, EPI>(ctx, KIND, A_, W_, B_, O_, T_dev, max_rows, N_, K_)                   \
+                   : launch_gemm<128, 128, EPI>(ctx, KIND, A_, W_, B_, O_, T_dev, max_rows, N_, K_)))
+            LEANN_GEMM(EPI_BIAS, LEANN_PROF_GEMM_QKV, x, w.wqkv, w.bqkv, qkv, 3 * d, d);
             {
                 ProfScope prof(ctx, LEANN_PROF_ATTENTION);
                 if (seq <= 128)
@@ -479,10 +474,10 @@ int enc_forward(leann_ctx *ctx, const leann_chunks *chunks, const int64_t *ids_d
                     hipLaunchKernelGGL(attention_kernel<8>, dim3(m, H), dim3(256), AttCfg<8>::SMEM, ctx->stream, qkv, cu,
                                        att, d, scale_log2e);
             }
-            LEANN_GEMM(EPI_BIAS_RES_F32, LEANN_PROF_GEMM_O, att, w.wo, w.bo, x, pre, d, d);
+            LEANN_GEMM(EPI_BIAS, LEANN_PROF_GEMM_O, att, w.wo, w.bo, delta, d, d);
             layer_norm(w.g1, w.be1);
-            LEANN_GEMM(EPI_BIAS_GELU, LEANN_PROF_GEMM_FFN1, x, w.w1, w.b1, nullptr, hid, F, d);
-            LEANN_GEMM(EPI_BIAS_RES_F32, LEANN_PROF_GEMM_FFN2, hid, w.w2, w.b2, x, pre, d, F);
+            LEANN_GEMM(EPI_BIAS_GELU, LEANN_PROF_GEMM_FFN1, x, w.w1, w.b1, hid, F, d);
+            LEANN_GEMM(EPI_BIAS, LEANN_PROF_GEMM_FFN2, hid, w.w2, w.b2, delta, d, F);
 #undef LEANN_GEMM
             layer_norm(w.g2, w.be2);
         }

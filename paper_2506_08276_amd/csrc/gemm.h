@@ -4,7 +4,8 @@
 
 namespace {
 
-// C[T][N] = A[T][K] * W[N][K]^T (+ epilogue).  bf16 operands, fp32 accumulation in MFMA 32x32x16.
+// C[T][N] = A[T][K] * W[N][K]^T + bias (optionally GELU), rounded to bf16.  bf16 operands, fp32 accumulation in
+// MFMA 32x32x16.
 // Block tile BM x BN, K-slabs of 32, WM x WN waves.  A slab row is four 16-byte chunks; chunk c of row r
 // lives at chunk position c ^ ((r >> 2) & 3), so the row-wise stores and the column-of-rows MFMA operand reads
 // both spread over all LDS banks.
@@ -16,7 +17,7 @@ namespace {
 // The 256x256 tile (eight waves of 128x64) halves the bytes fetched from L2 per flop compared with 128x128,
 // which is what bounds the small tile.  Each output element is one fixed-order sum over K: a row's result does
 // not depend on T.
-enum { EPI_BIAS = 0, EPI_BIAS_GELU = 1, EPI_BIAS_RES_F32 = 2 };
+enum { EPI_BIAS = 0, EPI_BIAS_GELU = 1 };
 
 // GELU(v) = v Phi(v) with the normal distribution function written as a logistic function of an odd polynomial,
 // Phi(v) ~ 1 / (1 + 2^(-v p(v^2))), p(u) = c0 + c1 u + c2 u^2 fitted to the exact erf form (minimax over |v| <= 9):
@@ -34,7 +35,7 @@ constexpr int GEMM_BK = 32;
 template <int BM, int BN, int WM, int WN, int EPI>
 __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4) ? 2 : 1) void gemm_kernel(
     const bf16_t *__restrict__ A, const bf16_t *__restrict__ W, const float *__restrict__ bias,
-    const bf16_t *__restrict__ res, void *__restrict__ out, const int32_t *__restrict__ T_dev, int N, int K, int tiles_n)
+    bf16_t *__restrict__ out, const int32_t *__restrict__ T_dev, int N, int K, int tiles_n)
 {
     constexpr int BK = GEMM_BK;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -203,8 +204,7 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4) ? 2 : 1) void gemm_ker
     // slice of LDS so that the global stores are 16 bytes per lane and whole 128-byte row segments per 8 lanes.
     __syncthreads();  // every wave is done with the operand stages
     constexpr int WCOLS = BN / WN;
-    constexpr bool RES = EPI == EPI_BIAS_RES_F32;
-    constexpr int EROW = WCOLS * (RES ? 4 : 2) + 16;  // staged row pitch in bytes (the pad spreads the banks)
+    constexpr int EROW = WCOLS * 2 + 16;  // staged row pitch in bytes (the pad spreads the banks)
     unsigned char *stg = smem + wave * 32 * EROW;
     const int col0 = tile_n * BN + wn * WCOLS;
     const int row0 = tile_m * BM + wm * (BM / WM);
@@ -213,48 +213,24 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4) ? 2 : 1) void gemm_ker
     for (int ni = 0; ni < TN; ++ni) bv[ni] = bias[col0 + ni * 32 + (lane & 31)];
     // write-out geometry: a wave-wide access covers RPI rows of CPRW 16-byte chunks.  The output is read by a later
     // kernel only: streaming stores keep it from displacing the operand slabs in L2 (measured: 3-7% per GEMM).
-    constexpr int CPRW = WCOLS / (RES ? 4 : 8), RPI = 64 / CPRW, NJ = 32 / RPI;
+    constexpr int CPRW = WCOLS / 8, RPI = 64 / CPRW, NJ = 32 / RPI;
     const int orow = lane / CPRW, och = lane % CPRW;
-    // the residual rows of 32-row group mi+1 are fetched (streaming: read once) while group mi is transposed and written
-    bf16x4 rv[2][RES ? NJ : 1];
-    if (RES) {
-#pragma unroll
-        for (int j = 0; j < NJ; ++j)
-            rv[0][j] = __builtin_nontemporal_load(reinterpret_cast<const bf16x4 *>(res + (size_t)(row0 + j * RPI + orow) * N + col0 + och * 4));
-    }
 #pragma unroll
     for (int mi = 0; mi < TM; ++mi) {
-        if (RES && mi + 1 < TM) {
-#pragma unroll
-            for (int j = 0; j < NJ; ++j)
-                rv[(mi + 1) & 1][j] =
-                    __builtin_nontemporal_load(reinterpret_cast<const bf16x4 *>(res + (size_t)(row0 + (mi + 1) * 32 + j * RPI + orow) * N + col0 + och * 4));
-        }
 #pragma unroll
         for (int ni = 0; ni < TN; ++ni)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int lr = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3), lcol = ni * 32 + (lane & 31);
                 const float v = acc[mi][ni][r] + bv[ni];
-                if (RES)
-                    *reinterpret_cast<float *>(stg + lr * EROW + lcol * 4) = v;
-                else
-                    *reinterpret_cast<bf16_t *>(stg + lr * EROW + lcol * 2) = (bf16_t)(EPI == EPI_BIAS_GELU ? gelu_erf(v) : v);
+                *reinterpret_cast<bf16_t *>(stg + lr * EROW + lcol * 2) = (bf16_t)(EPI == EPI_BIAS_GELU ? gelu_erf(v) : v);
             }
         __builtin_amdgcn_wave_barrier();  // LDS serves a wave's accesses in order: the reads below see the writes
 #pragma unroll
         for (int j = 0; j < NJ; ++j) {
             const int lr = j * RPI + orow;
-            const size_t o = (size_t)(row0 + mi * 32 + lr) * N + col0;
-            if (RES) {
-                f32x4 v = *reinterpret_cast<const f32x4 *>(stg + lr * EROW + och * 16);
-#pragma unroll
-                for (int i = 0; i < 4; ++i) v[i] += (float)rv[mi & 1][j][i];
-                __builtin_nontemporal_store(v, reinterpret_cast<f32x4 *>(reinterpret_cast<float *>(out) + o + och * 4));
-            } else {
-                const u32x4 v = *reinterpret_cast<const u32x4 *>(stg + lr * EROW + och * 16);
-                __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(reinterpret_cast<bf16_t *>(out) + o + och * 8));
-            }
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(stg + lr * EROW + och * 16);
+            __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(out + (size_t)(row0 + mi * 32 + lr) * N + col0 + och * 8));
         }
         __builtin_amdgcn_wave_barrier();
     }
