@@ -24,8 +24,8 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak (published)
 # HBM-side bytes per valid token per GEMM launch (average of the QKV, O, FFN1, FFN2 launches), from the rocprofv3
 # FETCH_SIZE / WRITE_SIZE runs summarised in profiles/encoder_seq256_hbm_traffic.md (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0
-# after calibration against a 1 GiB copy); the algorithmic minimum is 7.7 KB.
-GEMM_TRAFFIC_BYTES_PER_TOKEN = 12.9e3
+# after calibration against a 1 GiB copy); the algorithmic minimum is 6.15 KB.
+GEMM_TRAFFIC_BYTES_PER_TOKEN = 10.55e3
 
 
 def log(*a):
@@ -90,25 +90,90 @@ def recall_at_3(ids, gt):
     return hit / gt.numel()
 
 
-def encoder_throughput(L, torch, ctx, cfg, batch=512, seq=256, reps=3):
-    """Config-2 style: ragged batch, lengths uniform in [64, 256], uniform random token ids."""
+def encoder_throughput(L, torch, ctx, cfg, seq=256, reps=3, batches=(32, 64, 128, 256, 512, 2048, 4096)):
+    """Config-2 style encoder-only runs: ragged batches, lengths uniform in [64, 256], uniform random token ids.
+    The headline figures are those of the largest batch; `by_batch` holds chunks/s of every batch size."""
     import leann_inputs as li
-    tokens, lengths = li.uniform_chunks(batch * 4, seq, 1, cfg["vocab"], 64, seq, li.config_seed(2) + 1)
+    tokens, lengths = li.uniform_chunks(max(batches), seq, 1, cfg["vocab"], 64, seq, li.config_seed(2) + 1)
     t, l = torch.from_numpy(tokens).to("cuda:0"), torch.from_numpy(lengths).to("cuda:0")
     out = torch.empty((tokens.shape[0], cfg["hidden"]), dtype=torch.float32, device="cuda:0")
-    L.leann_embed(ctx, t, l, hidden=cfg["hidden"], out=out)
-    torch.cuda.synchronize()
-    best = None
-    for _ in range(reps):
-        t0 = time.perf_counter()
-        L.leann_embed(ctx, t, l, hidden=cfg["hidden"], out=out)
+    by_batch = {}
+    for b in batches:
+        tb, lb, ob = t[:b].contiguous(), l[:b].contiguous(), out[:b]
+        L.leann_embed(ctx, tb, lb, hidden=cfg["hidden"], out=ob)
         torch.cuda.synchronize()
-        dt = time.perf_counter() - t0
-        best = dt if best is None else min(best, dt)
-    fl = chunk_flops(cfg, lengths)
-    return {"chunks_per_s": tokens.shape[0] / best, "tflops_valid_tokens": fl / best / 1e12,
-            "mfma_util_pct": 100.0 * fl / best / 1e12 / PEAK_BF16_TFLOPS, "batch": int(tokens.shape[0]), "seq": seq,
-            "mean_len": float(lengths.mean())}
+        best = None
+        for _ in range(reps):
+            t0 = time.perf_counter()
+            L.leann_embed(ctx, tb, lb, hidden=cfg["hidden"], out=ob)
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            best = dt if best is None else min(best, dt)
+        fl = chunk_flops(cfg, lengths[:b])
+        by_batch[str(b)] = {"chunks_per_s": b / best, "tflops_valid_tokens": fl / best / 1e12}
+    top = by_batch[str(max(batches))]
+    return {"chunks_per_s": top["chunks_per_s"], "tflops_valid_tokens": top["tflops_valid_tokens"],
+            "mfma_util_pct": 100.0 * top["tflops_valid_tokens"] / PEAK_BF16_TFLOPS, "batch": int(max(batches)), "seq": seq,
+            "mean_len": float(lengths.mean()), "by_batch": by_batch}
+
+
+def encoder_only(args):
+    """--encoder-only: the seq-256 encoder runs alone (the command the encoder profiles are taken with), followed by a
+    1 GiB device copy whose known size calibrates the profiler's HBM byte counters."""
+    import torch
+    import leann_inputs as li
+    import paper_2506_08276_amd as L
+    L.load_library()
+    cfg = dict(li.BASE)
+    w = li.encoder_weights(cfg, li.config_seed(2), bf16_exact=True)
+    ctx = L.leann_create(cfg, torch.from_numpy(w).to("cuda:0").to(torch.bfloat16))
+    if args.max_tokens:
+        L.leann_set_limits(ctx, args.max_tokens, 0)
+    res = encoder_throughput(L, torch, ctx, cfg, batches=(2048,) if args.profile_pass else (32, 64, 128, 256, 512, 2048, 4096))
+    src = torch.empty(256 * 1024 * 1024, dtype=torch.float32, device="cuda:0").normal_()
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    L.leann_destroy(ctx)
+    print(json.dumps({"mode": "encoder-only", "encoder": res, "calibration_copy_bytes": int(src.numel() * 4)}), flush=True)
+
+
+def adc_microbench(args):
+    """--adc-microbench: leann_adc alone over random code tables of 2 M rows (64 MB, cache resident) and 64 M rows
+    (2 GB, the paper's corpus scale: served from HBM).  One JSON line per case; adc_kernel time from HIP events."""
+    import numpy as np
+    import torch
+    import leann_inputs as li
+    import paper_2506_08276_amd as L
+    L.load_library()
+    cfg = dict(li.TINY)
+    ctx = L.leann_create(cfg, torch.from_numpy(li.encoder_weights(cfg, 1)).to("cuda:0"))
+    d, m = 768, 32
+    rng = np.random.default_rng(0)
+    cb = (rng.standard_normal((m, 256, d // m)) * 0.05).astype(np.float32)
+    for n in (2_000_000, 64_000_000):
+        codes = torch.randint(0, 256, (n, m), dtype=torch.uint8, device="cuda:0")
+        pq = L.leann_pq_wrap(ctx, cb, codes)
+        for nq, nc in ((4096, 2048), (4096, 1024), (256, 1024), (4096, 64), (256, 64), (4096, 16), (256, 16)):
+            q = torch.randn(nq, d, device="cuda:0")
+            q = (q / q.norm(dim=1, keepdim=True)).contiguous()
+            cand = torch.randint(0, n, (nq, nc), dtype=torch.int32, device="cuda:0")
+            out = torch.empty((nq, nc), dtype=torch.float32, device="cuda:0")
+            L.leann_adc(ctx, q, pq, cand, out=out)
+            L.leann_profile_begin(ctx)
+            reps = 5
+            for _ in range(reps):
+                L.leann_adc(ctx, q, pq, cand, out=out)
+            p = L.leann_profile_end(ctx)
+            adc_ms, lut_ms = p["ms"]["adc"] / reps, p["ms"]["lut"] / reps
+            gb = nq * nc * 40 / 1e9  # 32 B code + 4 B id + 4 B score per candidate
+            print(json.dumps({"mode": "adc-microbench", "table_rows": n, "queries": nq, "candidates_per_query": nc,
+                              "adc_kernel_ms": adc_ms, "lut_kernel_ms": lut_ms, "algorithmic_GBps": gb / (adc_ms * 1e-3),
+                              "frac_of_8TBps": gb / (adc_ms * 1e-3) / 8000.0,
+                              "incl_lut_loads_GBps": (gb + nq * 32768 / 1e9) / (adc_ms * 1e-3)}), flush=True)
+        L.leann_pq_free(pq)
+        del codes, pq
+    L.leann_destroy(ctx)
 
 
 def cpu_baseline(world, recomputed_per_query, seconds_target=15.0):
@@ -158,6 +223,9 @@ def main():
     ap.add_argument("--pq-iters", type=int, default=10)
     ap.add_argument("--target-recall", type=float, default=0.90)
     ap.add_argument("--max-tokens", type=int, default=0, help="padded tokens per encoder pass (0 = library default)")
+    ap.add_argument("--encoder-only", action="store_true", help="run only the seq-256 encoder batches (profiling aid)")
+    ap.add_argument("--profile-pass", action="store_true", help="with --encoder-only: a single 2048-chunk batch")
+    ap.add_argument("--adc-microbench", action="store_true", help="run only the stand-alone ADC scorer table")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-encoder-bench", action="store_true")
     args = ap.parse_args()
@@ -165,6 +233,10 @@ def main():
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 (queries would shard across GPUs with a "
               "replicated index, which is not built here)", file=sys.stderr)
         sys.exit(2)
+    if args.encoder_only:
+        return encoder_only(args)
+    if args.adc_microbench:
+        return adc_microbench(args)
 
     import torch
     import paper_2506_08276_amd as L
