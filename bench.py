@@ -176,6 +176,32 @@ def adc_microbench(args):
     L.leann_destroy(ctx)
 
 
+def hub_cache_leg(L, torch, world, args, ef, qps_plain, ids_plain):
+    """The same search with stored embeddings for the highest-degree nodes (App. D, relaxed storage budget): one
+    untimed and one timed step; the stored rows are the device's own embeddings, so the answers must not change."""
+    import leann_inputs as li
+    g = world["graph"]
+    row_ptr, col_idx = g[0].cpu().numpy(), g[1].cpu().numpy().view("uint32")
+    ids_hub, slot_of = li.hub_slots(row_ptr, col_idx, args.cache_frac)
+    dev = torch.device("cuda:0")
+    rows = world["emb"][torch.from_numpy(ids_hub).to(dev)].contiguous()
+    cache = (torch.from_numpy(slot_of).to(dev), rows)
+
+    def run():
+        return L.leann_search(world["ctx"], world["queries"], g, world["pq"], world["t"], world["l"], ef, args.k,
+                              args.rerank_ratio, args.batch, cache=cache)
+    run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ids, _, st = run()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    return {"stored_fraction": args.cache_frac, "stored_rows": int(len(ids_hub)),
+            "hit_rate": st["cache_hits"] / st["recomputed_chunks"], "queries_per_s": args.nq / dt,
+            "speedup": args.nq / dt / qps_plain, "same_answers": bool(torch.equal(ids, ids_plain)),
+            "encoded_chunks_per_query": st["encoded_chunks"] / args.nq}
+
+
 def cpu_baseline(world, recomputed_per_query, seconds_target=15.0):
     """The oracle as it stands, on a bounded sample of the same workload: oracle chunks/s over a few chunks per
     core, and queries/s derived as chunks/s / (recomputed chunks per query measured on the GPU run)."""
@@ -222,6 +248,8 @@ def main():
     ap.add_argument("--batch", type=int, default=64)
     ap.add_argument("--pq-iters", type=int, default=10)
     ap.add_argument("--target-recall", type=float, default=0.90)
+    ap.add_argument("--cache-frac", type=float, default=0.10,
+                    help="extra leg: store the embeddings of this fraction of the nodes (highest degree); 0 = skip")
     ap.add_argument("--max-tokens", type=int, default=0, help="padded tokens per encoder pass (0 = library default)")
     ap.add_argument("--encoder-only", action="store_true", help="run only the seq-256 encoder batches (profiling aid)")
     ap.add_argument("--profile-pass", action="store_true", help="with --encoder-only: a single 2048-chunk batch")
@@ -325,6 +353,8 @@ def main():
                      if gemm_launches else None},
         "kernel_ms": {k: v / args.steps for k, v in prof["ms"].items()},
     }
+    if args.cache_frac > 0:
+        out["hub_cache"] = hub_cache_leg(L, torch, world, args, ef, qps, ids)
     if not args.no_encoder_bench:
         out["encoder"] = encoder_throughput(L, torch, ctx, cfg)
     if not args.no_cpu_baseline:

@@ -87,6 +87,7 @@ typedef struct {
     int64_t encoded_tokens;    /* valid tokens of those chunks */
     int64_t flushes;           /* per-query batch flushes */
     int64_t rounds;            /* traverse -> encode -> insert rounds over the whole query set */
+    int64_t cache_hits;        /* exact scores served by the stored-embedding table (part of recomputed_chunks) */
     float encoder_ms, traverse_ms, total_ms; /* device time (HIP events) */
 } leann_search_stats;
 

@@ -8,4 +8,4 @@ from .configs import TINY, BASE, BASE_S128, SEED0, config_seed  # noqa: F401
 from .weights import encoder_weights, weight_layout, to_bf16_exact  # noqa: F401
 from .chunks import (uniform_chunks, topic_chunks, make_topics, family_corpus, family_queries,  # noqa: F401
                      make_latent_space, latent_corpus, latent_queries)  # noqa: F401
-from .graphs import knn_graph, navigable_fixture, to_csr, add_ring, max_in_degree_node  # noqa: F401
+from .graphs import knn_graph, navigable_fixture, to_csr, add_ring, max_in_degree_node, hub_slots  # noqa: F401

@@ -45,6 +45,20 @@ def max_in_degree_node(nbr, n=None):
     return int(np.argmax(indeg)), indeg
 
 
+def hub_slots(row_ptr, col_idx, frac):
+    """Stored-embedding table layout for the nodes of highest degree in a CSR graph: the ceil(frac * n) nodes with the
+    largest in-degree + out-degree (ties: lower id), in id order.  Returns (ids int64 [rows], slot_of int32 [n])
+    with slot_of[v] = row of v in the table, -1 for the others."""
+    n = len(row_ptr) - 1
+    deg = np.diff(np.asarray(row_ptr).astype(np.int64)) + np.bincount(np.asarray(col_idx).astype(np.int64), minlength=n)
+    rows = int(np.ceil(frac * n))
+    order = np.lexsort((np.arange(n), -deg))
+    ids = np.sort(order[:rows]).astype(np.int64)
+    slot_of = np.full(n, -1, dtype=np.int32)
+    slot_of[ids] = np.arange(rows, dtype=np.int32)
+    return ids, slot_of
+
+
 def to_csr(lists):
     """Adjacency (2-D array or list of 1-D arrays) -> (row_ptr uint64 [n+1], col_idx uint32 [E])."""
     lens = np.array([len(r) for r in lists], dtype=np.uint64)

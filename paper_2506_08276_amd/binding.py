@@ -51,7 +51,7 @@ class EmbCache(C.Structure):
 class SearchStats(C.Structure):
     _fields_ = [("hops", C.c_int64), ("adc_candidates", C.c_int64), ("recomputed_chunks", C.c_int64),
                 ("encoded_chunks", C.c_int64), ("encoded_tokens", C.c_int64), ("flushes", C.c_int64),
-                ("rounds", C.c_int64), ("encoder_ms", C.c_float), ("traverse_ms", C.c_float),
+                ("rounds", C.c_int64), ("cache_hits", C.c_int64), ("encoder_ms", C.c_float), ("traverse_ms", C.c_float),
                 ("total_ms", C.c_float)]
 
     def as_dict(self):

@@ -39,7 +39,7 @@ struct SearchState {
     int32_t ef, aqcap, pcap;
 };
 
-enum { CTR_HOPS = 0, CTR_ADC, CTR_RECOMP, CTR_FLUSH, CTR_PENDING, CTR_NENC, CTR_ERR, CTR_TOKENS, CTR_MAXDEG, CTR_COUNT };
+enum { CTR_HOPS = 0, CTR_ADC, CTR_RECOMP, CTR_FLUSH, CTR_PENDING, CTR_NENC, CTR_ERR, CTR_TOKENS, CTR_MAXDEG, CTR_HITS, CTR_COUNT };
 enum { ERR_BAD_NEIGHBOUR = 1, ERR_AQ_OVERFLOW = 2, ERR_P_OVERFLOW = 4 };
 
 __device__ inline bool better(float sa, uint32_t ia, float sb, uint32_t ib) { return sa > sb || (sa == sb && ia < ib); }
@@ -245,10 +245,18 @@ __global__ __launch_bounds__(64) void claim_kernel(SearchState s, const int32_t 
 {
     const int q = blockIdx.x;
     const int np = s.n_pend[q];
+    int hits = 0;
     for (int j = threadIdx.x; j < np; j += 64) {
         const uint32_t c = s.pend[(size_t)q * s.pcap + j];
-        if (slot_of && slot_of[c] >= 0) continue;
+        if (slot_of && slot_of[c] >= 0) {
+            ++hits;
+            continue;
+        }
         atomicMin(&s.owner[c], q * s.pcap + j);
+    }
+    if (slot_of) {
+        for (int o = 32; o; o >>= 1) hits += __shfl_xor(hits, o);
+        if (threadIdx.x == 0 && hits) atomicAdd((unsigned long long *)&s.counters[CTR_HITS], (unsigned long long)hits);
     }
 }
 
@@ -602,6 +610,7 @@ int search_run(leann_ctx *ctx, const float *queries_dev, int64_t nq, const leann
         stats->hops = h_ctr[CTR_HOPS];
         stats->adc_candidates = h_ctr[CTR_ADC];
         stats->recomputed_chunks = h_ctr[CTR_RECOMP];
+        stats->cache_hits = h_ctr[CTR_HITS];
         stats->encoded_chunks = encoded;
         stats->encoded_tokens = h_ctr[CTR_TOKENS];
         stats->flushes = h_ctr[CTR_FLUSH];

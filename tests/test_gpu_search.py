@@ -60,6 +60,7 @@ def test_search_logic_exact_with_stored_embeddings(L, orc, world, ef, k, alpha, 
                       ("flushes", "flushes")):
         assert st[key] == sum(r["stats"][okey] for r in runs), key
     assert st["encoded_chunks"] == 0  # everything came from the stored table
+    assert st["cache_hits"] == st["recomputed_chunks"]
 
 
 def test_result_independent_of_concurrency(L, world):
@@ -73,6 +74,35 @@ def test_result_independent_of_concurrency(L, world):
         assert torch.equal(ids1[0], ids_all[qi]) and torch.equal(sc1[0], sc_all[qi])
     ids_again, sc_again, _ = L.leann_search(w["ctx"], w["q"], w["graph"], w["pq"], w["t"], w["l"], 32, 3, 0.2, 32)
     assert torch.equal(ids_again, ids_all) and torch.equal(sc_again, sc_all)
+
+
+def test_hub_embedding_cache_changes_work_not_results(L, world):
+    """Stored embeddings for the highest-degree 10 % of the nodes (App. D, relaxed storage budget): a hit skips the
+    encoder, the answer and the trajectory stay the same because the stored rows are the encoder's own output."""
+    import torch
+    import leann_inputs as li
+    w = world
+    ids_hub, slot_of = li.hub_slots(w["row_ptr"], w["col_idx"], 0.10)
+    say(f"hub cache: {len(ids_hub)} of {w['n']} nodes stored")
+    rows = L.leann_embed(w["ctx"], w["t"], w["l"], hidden=w["cfg"]["hidden"], ids=to_dev(ids_hub))
+    cache = (to_dev(slot_of), rows)
+    args = (w["graph"], w["pq"], w["t"], w["l"], 32, 3, 0.2, 32)
+    ids0, sc0, st0 = L.leann_search(w["ctx"], w["q"], *args)
+    ids1, sc1, st1 = L.leann_search(w["ctx"], w["q"], *args, cache=cache)
+    assert torch.equal(ids0, ids1) and torch.equal(sc0, sc1)
+    for key in ("hops", "adc_candidates", "recomputed_chunks", "flushes"):
+        assert st0[key] == st1[key], key
+    assert st0["cache_hits"] == 0 and 0 < st1["cache_hits"] < st1["recomputed_chunks"]
+    assert st1["encoded_chunks"] < st0["encoded_chunks"]
+    # one query alone shares nothing: every request is either a hit or an encoder row
+    hits = 0
+    for qi in range(w["q"].shape[0]):
+        _, _, s1 = L.leann_search(w["ctx"], w["q"][qi:qi + 1].contiguous(), *args, cache=cache)
+        assert s1["cache_hits"] + s1["encoded_chunks"] == s1["recomputed_chunks"]
+        hits += s1["cache_hits"]
+    assert hits == st1["cache_hits"]
+    print(f"hub cache 10%: hit rate {st1['cache_hits'] / st1['recomputed_chunks']:.3f}, encoded chunks "
+          f"{st0['encoded_chunks']} -> {st1['encoded_chunks']}")
 
 
 def decided_ranks(log_scores, k, gap=1e-3):
