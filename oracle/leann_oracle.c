@@ -547,11 +547,51 @@ typedef struct {
  * log_ids/log_scores (nullable, capacity log_cap): every exactly scored
  * node in scoring order.  visit_order (nullable): the u of every hop.
  */
+/*
+ * Pending index updates that the output stage of a search takes into account
+ * (App. B "Soft Deletion Strategy" and "Batched Add Operation"):
+ *  - deleted[v] != 0: node v is soft-deleted.  It is still traversed (its
+ *    adjacency list is untouched); the exact queue is filtered by the flag
+ *    before the k best active entries are taken.
+ *  - buf_emb[buf_n][d], buf_ids[buf_n]: embeddings of added chunks that are
+ *    not inserted into the graph yet.  They are scanned exhaustively
+ *    (<q, e>, the exact score of Eq. 1) and merged with the graph's result
+ *    under the same order (score descending, id ascending).
+ * Reading where the text is silent: a buffered id is not subject to the
+ * delete flags (they cover graph nodes), and buffered entries never enter
+ * the traversal.
+ */
+typedef struct {
+    const uint8_t *deleted; /* [n] or NULL */
+    const float *buf_emb;   /* [buf_n][d] or NULL */
+    const int64_t *buf_ids; /* [buf_n] */
+    int64_t buf_n;
+} orc_updates;
+
+static int search_core(const float *q, int32_t d, const uint64_t *row_ptr, const uint32_t *col_idx, int64_t n,
+                       uint32_t entry, const float *codebook, const uint8_t *codes, int32_t m_sub, orc_embed_fn embed,
+                       void *user, int32_t ef, int32_t k, float alpha, int32_t batch, int32_t alpha_mode,
+                       const orc_updates *upd, int64_t *out_ids, float *out_scores, orc_search_stats *stats,
+                       int64_t *log_ids, float *log_scores, int64_t log_cap, int64_t *log_n, int64_t *visit_order,
+                       int64_t visit_cap, int64_t *visit_n);
+
 int orc_search(const float *q, int32_t d, const uint64_t *row_ptr, const uint32_t *col_idx, int64_t n,
                uint32_t entry, const float *codebook, const uint8_t *codes, int32_t m_sub, orc_embed_fn embed,
                void *user, int32_t ef, int32_t k, float alpha, int32_t batch, int32_t alpha_mode,
                int64_t *out_ids, float *out_scores, orc_search_stats *stats, int64_t *log_ids, float *log_scores,
                int64_t log_cap, int64_t *log_n, int64_t *visit_order, int64_t visit_cap, int64_t *visit_n)
+{
+    return search_core(q, d, row_ptr, col_idx, n, entry, codebook, codes, m_sub, embed, user, ef, k, alpha, batch,
+                       alpha_mode, NULL, out_ids, out_scores, stats, log_ids, log_scores, log_cap, log_n, visit_order,
+                       visit_cap, visit_n);
+}
+
+static int search_core(const float *q, int32_t d, const uint64_t *row_ptr, const uint32_t *col_idx, int64_t n,
+                       uint32_t entry, const float *codebook, const uint8_t *codes, int32_t m_sub, orc_embed_fn embed,
+                       void *user, int32_t ef, int32_t k, float alpha, int32_t batch, int32_t alpha_mode,
+                       const orc_updates *upd, int64_t *out_ids, float *out_scores, orc_search_stats *stats,
+                       int64_t *log_ids, float *log_scores, int64_t log_cap, int64_t *log_n, int64_t *visit_order,
+                       int64_t visit_cap, int64_t *visit_n)
 {
     if (!q || !row_ptr || !col_idx || !codebook || !codes || !embed || !out_ids || !out_scores) return ORC_EINVAL;
     if (k < 1 || k > ef || !(alpha > 0.f) || alpha > 1.f || batch < 1 || d % m_sub || entry >= (uint64_t)n)
@@ -641,19 +681,42 @@ int orc_search(const float *q, int32_t d, const uint64_t *row_ptr, const uint32_
         }
         if (!has_unvisited && n_pend == 0) break;
     }
-    /* k best of EQ */
-    for (int j = 0; j < k; ++j) {
-        int64_t b = -1;
-        for (int64_t i = 0; i < n_eq; ++i)
-            if (eq[i].visited >= 0 && (b < 0 || better(eq[i].score, eq[i].id, eq[b].score, eq[b].id))) b = i;
-        if (b < 0) {
-            out_ids[j] = -1;
-            out_scores[j] = -INFINITY;
-        } else {
-            out_ids[j] = eq[b].id;
-            out_scores[j] = eq[b].score;
-            eq[b].visited = -1; /* taken */
+    /* Output: the k best of EQ.  With pending updates: the k best of (EQ without
+     * soft-deleted nodes) united with the exhaustively scored add buffer. */
+    {
+        const int64_t nb = (upd && upd->buf_emb) ? upd->buf_n : 0;
+        float *bs = nb ? malloc(sizeof(float) * (size_t)nb) : NULL;
+        uint8_t *btaken = nb ? calloc((size_t)nb, 1) : NULL;
+        if (nb && (!bs || !btaken)) { free(bs); free(btaken); rc = ORC_ENOMEM; goto done; }
+        for (int64_t b = 0; b < nb; ++b) {
+            float sc = 0.f;
+            for (int i = 0; i < d; ++i) sc += q[i] * upd->buf_emb[b * d + i];
+            bs[b] = sc;
         }
+        if (upd && upd->deleted)
+            for (int64_t i = 0; i < n_eq; ++i)
+                if (upd->deleted[eq[i].id]) eq[i].visited = -1; /* filtered out */
+        for (int j = 0; j < k; ++j) {
+            int64_t b = -1, bb = -1;
+            for (int64_t i = 0; i < n_eq; ++i)
+                if (eq[i].visited >= 0 && (b < 0 || better(eq[i].score, eq[i].id, eq[b].score, eq[b].id))) b = i;
+            for (int64_t i = 0; i < nb; ++i)
+                if (!btaken[i] && (bb < 0 || better(bs[i], upd->buf_ids[i], bs[bb], upd->buf_ids[bb]))) bb = i;
+            const int from_buf = bb >= 0 && (b < 0 || better(bs[bb], upd->buf_ids[bb], eq[b].score, eq[b].id));
+            if (from_buf) {
+                out_ids[j] = upd->buf_ids[bb];
+                out_scores[j] = bs[bb];
+                btaken[bb] = 1;
+            } else if (b >= 0) {
+                out_ids[j] = eq[b].id;
+                out_scores[j] = eq[b].score;
+                eq[b].visited = -1; /* taken */
+            } else {
+                out_ids[j] = -1;
+                out_scores[j] = -INFINITY;
+            }
+        }
+        free(bs); free(btaken);
     }
 done:
     if (stats) *stats = st;
@@ -704,6 +767,23 @@ int orc_search_table(const float *q, int32_t d, const uint64_t *row_ptr, const u
     return orc_search(q, d, row_ptr, col_idx, n, entry, codebook, codes, m_sub, embed_from_table, &u, ef, k, alpha,
                       batch, alpha_mode, out_ids, out_scores, stats, log_ids, log_scores, log_cap, log_n,
                       visit_order, visit_cap, visit_n);
+}
+
+/* orc_search_table with pending updates (soft-delete flags, add buffer). */
+int orc_search_table_updates(const float *q, int32_t d, const uint64_t *row_ptr, const uint32_t *col_idx, int64_t n,
+                             uint32_t entry, const float *codebook, const uint8_t *codes, int32_t m_sub,
+                             const float *table, int32_t ef, int32_t k, float alpha, int32_t batch, int32_t alpha_mode,
+                             const uint8_t *deleted, const float *buf_emb, const int64_t *buf_ids, int64_t buf_n,
+                             int64_t *out_ids, float *out_scores, orc_search_stats *stats, int64_t *log_ids,
+                             float *log_scores, int64_t log_cap, int64_t *log_n, int64_t *visit_order,
+                             int64_t visit_cap, int64_t *visit_n)
+{
+    table_user u = {table, d};
+    orc_updates upd = {deleted, buf_emb, buf_ids, buf_n};
+    if (buf_n < 0 || (buf_n > 0 && (!buf_emb || !buf_ids))) return ORC_EINVAL;
+    return search_core(q, d, row_ptr, col_idx, n, entry, codebook, codes, m_sub, embed_from_table, &u, ef, k, alpha,
+                       batch, alpha_mode, &upd, out_ids, out_scores, stats, log_ids, log_scores, log_cap, log_n,
+                       visit_order, visit_cap, visit_n);
 }
 
 /* orc_search with true recomputation: every flush runs the encoder oracle. */

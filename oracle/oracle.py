@@ -196,8 +196,11 @@ def _search_common(call, n, ef, k):
     }
 
 
-def search_table(q, row_ptr, col_idx, entry, codebook, codes, table, ef, k, alpha, batch, alpha_mode=0):
-    """Algorithm 2 + dynamic batching with exact embeddings looked up in `table`."""
+def search_table(q, row_ptr, col_idx, entry, codebook, codes, table, ef, k, alpha, batch, alpha_mode=0,
+                 deleted=None, buffer=None):
+    """Algorithm 2 + dynamic batching with exact embeddings looked up in `table`.
+    deleted: optional uint8 flags [n] (soft-deleted nodes, filtered at the output stage);
+    buffer: optional (ids int64 [nb], emb float32 [nb][d]) of added chunks that are scanned exhaustively."""
     lib = _load()
     q = _f32(q)
     table = _f32(table)
@@ -207,7 +210,28 @@ def search_table(q, row_ptr, col_idx, entry, codebook, codes, table, ef, k, alph
     n, d = table.shape
     m_sub = codebook.shape[0]
 
+    if deleted is not None:
+        deleted = np.ascontiguousarray(deleted, dtype=np.uint8)
+        assert deleted.shape == (n,)
+    buf_ids = buf_emb = None
+    if buffer is not None:
+        buf_ids = np.ascontiguousarray(buffer[0], dtype=np.int64)
+        buf_emb = _f32(buffer[1])
+        assert buf_emb.shape == (len(buf_ids), d)
+
     def call(out_ids, out_sc, st, log_ids, log_sc, cap, log_n, visit, visit_n):
+        if deleted is not None or buffer is not None:
+            return lib.orc_search_table_updates(
+                _p(q, C.c_float), C.c_int32(d), _p(row_ptr, C.c_uint64), _p(col_idx, C.c_uint32), C.c_int64(n),
+                C.c_uint32(entry), _p(codebook, C.c_float), _p(codes, C.c_uint8), C.c_int32(m_sub),
+                _p(table, C.c_float), C.c_int32(ef), C.c_int32(k), C.c_float(alpha), C.c_int32(batch),
+                C.c_int32(alpha_mode), _p(deleted, C.c_uint8) if deleted is not None else None,
+                _p(buf_emb, C.c_float) if buffer is not None else None,
+                _p(buf_ids, C.c_int64) if buffer is not None else None,
+                C.c_int64(len(buf_ids) if buffer is not None else 0),
+                _p(out_ids, C.c_int64), _p(out_sc, C.c_float), C.byref(st),
+                _p(log_ids, C.c_int64), _p(log_sc, C.c_float), C.c_int64(cap), C.byref(log_n),
+                _p(visit, C.c_int64), C.c_int64(cap), C.byref(visit_n))
         return lib.orc_search_table(
             _p(q, C.c_float), C.c_int32(d), _p(row_ptr, C.c_uint64), _p(col_idx, C.c_uint32), C.c_int64(n),
             C.c_uint32(entry), _p(codebook, C.c_float), _p(codes, C.c_uint8), C.c_int32(m_sub),

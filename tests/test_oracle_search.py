@@ -265,3 +265,64 @@ def test_search_with_true_recomputation_equals_table_lookup(orc):
                                alpha=0.3, batch=4)
         assert list(a["ids"]) == list(b["ids"]) and a["stats"] == b["stats"]
         assert np.array_equal(a["scores"], b["scores"])
+
+
+# ---------------------------------------------------------------- pending updates (App. B)
+def top_ef_of_log(r, ef):
+    """The exact queue at the end of a search = the best ef of everything exactly scored (score desc, id asc)."""
+    order = np.lexsort((r["log_ids"], -r["log_scores"].astype(np.float64)))[:ef]
+    return r["log_ids"][order], r["log_scores"][order]
+
+
+def test_soft_delete_filters_the_exact_queue_not_the_traversal(orc, world):
+    w, ef, k = world, 24, 5
+    rng = np.random.default_rng(11)
+    for qi, q in enumerate(w["queries"][:6]):
+        plain = orc.search_table(q, w["row_ptr"], w["col_idx"], w["entry"], w["cb"], w["codes"], w["table"], ef, k, 0.3, 4)
+        deleted = np.zeros(w["n"], np.uint8)
+        deleted[plain["ids"][[0, 2]]] = 1                       # two of the answers ...
+        deleted[rng.integers(0, w["n"], 40)] = 1                # ... and a random 10 %
+        r = orc.search_table(q, w["row_ptr"], w["col_idx"], w["entry"], w["cb"], w["codes"], w["table"], ef, k, 0.3, 4,
+                             deleted=deleted)
+        # deleted nodes are still traversed: the trajectory and every count are those of the plain search
+        assert list(r["visit_order"]) == list(plain["visit_order"]) and list(r["log_ids"]) == list(plain["log_ids"])
+        assert r["stats"] == plain["stats"]
+        # the answer is the exact queue without the flagged nodes, first k (written out independently)
+        eq_ids, eq_sc = top_ef_of_log(plain, ef)
+        keep = [i for i in range(len(eq_ids)) if not deleted[eq_ids[i]]][:k]
+        want = list(eq_ids[keep]) + [-1] * (k - len(keep))
+        assert list(r["ids"]) == want and not any(deleted[i] for i in r["ids"] if i >= 0)
+        np.testing.assert_array_equal(r["scores"][:len(keep)], eq_sc[keep])
+    # everything deleted: nothing to return
+    r = orc.search_table(w["queries"][0], w["row_ptr"], w["col_idx"], w["entry"], w["cb"], w["codes"], w["table"], ef, k,
+                         0.3, 4, deleted=np.ones(w["n"], np.uint8))
+    assert list(r["ids"]) == [-1] * k and np.all(np.isneginf(r["scores"]))
+
+
+def test_add_buffer_is_scanned_and_merged(orc, world):
+    w, ef, k = world, 24, 5
+    rng = np.random.default_rng(12)
+    nb = 30
+    buf_ids = np.arange(w["n"], w["n"] + nb, dtype=np.int64)
+    for qi, q in enumerate(w["queries"][:6]):
+        # buffered chunks: a few near the query (they must surface), the rest random
+        near = unit(q[None, :] + 0.15 * rng.standard_normal((4, w["d"])))
+        buf = np.concatenate([near, unit(rng.standard_normal((nb - 4, w["d"])))]).astype(np.float32)
+        plain = orc.search_table(q, w["row_ptr"], w["col_idx"], w["entry"], w["cb"], w["codes"], w["table"], ef, k, 0.3, 4)
+        r = orc.search_table(q, w["row_ptr"], w["col_idx"], w["entry"], w["cb"], w["codes"], w["table"], ef, k, 0.3, 4,
+                             buffer=(buf_ids, buf))
+        assert list(r["visit_order"]) == list(plain["visit_order"]) and r["stats"] == plain["stats"]
+        # brute force over (exact queue) U (buffer), written out independently
+        eq_ids, eq_sc = top_ef_of_log(plain, ef)
+        bs = np.array([np.float32(sum(np.float32(a) * np.float32(b) for a, b in zip(q, e))) for e in buf], np.float32)
+        ids = np.concatenate([eq_ids, buf_ids])
+        sc = np.concatenate([eq_sc, bs])
+        order = np.lexsort((ids, -sc.astype(np.float64)))[:k]
+        assert list(r["ids"]) == list(ids[order])
+        np.testing.assert_allclose(r["scores"], sc[order], rtol=0, atol=1e-6)
+        assert any(i >= w["n"] for i in r["ids"])           # the near-duplicates of the query do surface
+    # both kinds of update together, and k larger than what is left
+    deleted = np.ones(w["n"], np.uint8)
+    r = orc.search_table(w["queries"][0], w["row_ptr"], w["col_idx"], w["entry"], w["cb"], w["codes"], w["table"], ef, k,
+                         0.3, 4, deleted=deleted, buffer=(buf_ids[:3], buf[:3]))
+    assert sorted(r["ids"][:3]) == list(buf_ids[:3]) and list(r["ids"][3:]) == [-1, -1]
