@@ -78,6 +78,22 @@ typedef struct {
     int64_t rows;
 } leann_emb_cache;
 
+/* Pending index updates seen by the output stage of a search (App. B "Soft
+ * Deletion Strategy", "Batched Add Operation"):
+ *   deleted_bits: bit (v & 31) of word (v >> 5) set = node v is soft-deleted; (n + 31) / 32
+ *     words.  Deleted nodes are traversed as before (their adjacency lists stay); the exact
+ *     queue is filtered by the flag before the k best active entries are returned.
+ *   buffer_emb fp32[buffer_n][hidden], buffer_ids[buffer_n]: embeddings of added chunks that
+ *     are not inserted into the graph yet.  Every one is scored exactly (<q, e>) and merged
+ *     with the graph's result under (score descending, id ascending).
+ * Device pointers, borrowed for the call; either part may be absent (NULL / 0). */
+typedef struct {
+    const uint32_t *deleted_bits;
+    const float *buffer_emb;
+    const uint32_t *buffer_ids;
+    int64_t buffer_n;
+} leann_updates;
+
 /* Per-call totals over all queries of a leann_search call. */
 typedef struct {
     int64_t hops;              /* exploration steps (Alg. 2 "read the closest unvisited node") */
@@ -185,6 +201,14 @@ int leann_search(leann_ctx *ctx, const float *queries_dev, int64_t nq, const lea
                  const leann_pq *pq, const leann_chunks *chunks, const leann_emb_cache *cache, int32_t ef,
                  int32_t k, float rerank_ratio, int32_t batch, int64_t *out_ids_dev, float *out_scores_dev,
                  leann_search_stats *stats_host);
+
+/* leann_search with pending updates (see leann_updates); updates == NULL is leann_search.
+ * Errors as leann_search, plus LEANN_EINVAL for a buffer with null pointers or more than
+ * 2^24 rows. */
+int leann_search_updates(leann_ctx *ctx, const float *queries_dev, int64_t nq, const leann_graph *graph,
+                         const leann_pq *pq, const leann_chunks *chunks, const leann_emb_cache *cache,
+                         const leann_updates *updates, int32_t ef, int32_t k, float rerank_ratio, int32_t batch,
+                         int64_t *out_ids_dev, float *out_scores_dev, leann_search_stats *stats_host);
 
 /* Tuning knobs (all optional): largest number of tokens one encoder pass holds
  * (workspace size), and the per-query capacity of the approximate queue. */

@@ -20,6 +20,7 @@ STATUS = {0: "LEANN_OK", -1: "LEANN_EINVAL", -2: "LEANN_ENOMEM", -3: "LEANN_EDEV
           -5: "LEANN_ECAPACITY"}
 EXPORTS = ["leann_last_error", "leann_create", "leann_destroy", "leann_embed", "leann_build_pq", "leann_pq_export",
            "leann_pq_import", "leann_pq_wrap", "leann_pq_info", "leann_pq_free", "leann_adc", "leann_search",
+           "leann_search_updates",
            "leann_set_limits", "leann_profile_begin", "leann_profile_end"]
 PROF_KINDS = ["gemm_qkv", "gemm_o", "gemm_ffn1", "gemm_ffn2", "attention", "layernorm", "enc_other", "traverse",
               "collect", "score_insert", "lut", "adc"]
@@ -202,7 +203,20 @@ def leann_adc(ctx, queries, pq, cand_ids, out=None):
     return out
 
 
-def leann_search(ctx, queries, graph, pq, tokens, lengths, ef, k, rerank_ratio, batch, cache=None):
+class Updates(C.Structure):
+    _fields_ = [("deleted_bits", C.c_void_p), ("buffer_emb", C.c_void_p), ("buffer_ids", C.c_void_p),
+                ("buffer_n", C.c_int64)]
+
+
+def leann_search_updates(ctx, queries, graph, pq, tokens, lengths, ef, k, rerank_ratio, batch, cache=None,
+                         deleted_bits=None, buffer=None):
+    """leann_search with pending updates: deleted_bits = int32 CUDA tensor of (n + 31) // 32 words (bit v set: node v
+    is soft-deleted) or None; buffer = (ids int32 CUDA tensor holding uint32 [nb], emb float32 [nb][d]) or None."""
+    return leann_search(ctx, queries, graph, pq, tokens, lengths, ef, k, rerank_ratio, batch, cache=cache,
+                        _updates=(deleted_bits, buffer))
+
+
+def leann_search(ctx, queries, graph, pq, tokens, lengths, ef, k, rerank_ratio, batch, cache=None, _updates=None):
     """graph = (row_ptr int64 CUDA tensor holding uint64 values, col_idx int32 CUDA tensor holding uint32, entry).
     cache = (slot_of int32 [n], emb float32 [rows][d]) or None.
     Returns (ids int64 [nq][k], scores float32 [nq][k], stats dict)."""
@@ -223,6 +237,23 @@ def leann_search(ctx, queries, graph, pq, tokens, lengths, ef, k, rerank_ratio, 
         _dev(emb, torch.float32, "cache emb")
         cstruct = EmbCache(slot_of.data_ptr(), emb.data_ptr(), emb.shape[0])
         cref = C.byref(cstruct)
+    if _updates is not None:
+        deleted_bits, buffer = _updates
+        u = Updates(None, None, None, 0)
+        if deleted_bits is not None:
+            _dev(deleted_bits, torch.int32, "deleted_bits")
+            assert deleted_bits.numel() >= (g.n + 31) // 32
+            u.deleted_bits = deleted_bits.data_ptr()
+        if buffer is not None:
+            buf_ids, buf_emb = buffer
+            _dev(buf_ids, torch.int32, "buffer ids")
+            _dev(buf_emb, torch.float32, "buffer emb")
+            assert buf_emb.shape == (buf_ids.numel(), queries.shape[1])
+            u.buffer_emb, u.buffer_ids, u.buffer_n = buf_emb.data_ptr(), buf_ids.data_ptr(), buf_ids.numel()
+        _check(load_library().leann_search_updates(ctx, _ptr(queries), C.c_int64(nq), C.byref(g), pq, C.byref(ch), cref,
+                                                   C.byref(u), C.c_int32(ef), C.c_int32(k), C.c_float(rerank_ratio),
+                                                   C.c_int32(batch), _ptr(ids), _ptr(scores), C.byref(st)))
+        return ids, scores, st.as_dict()
     _check(load_library().leann_search(ctx, _ptr(queries), C.c_int64(nq), C.byref(g), pq, C.byref(ch), cref,
                                        C.c_int32(ef), C.c_int32(k), C.c_float(rerank_ratio), C.c_int32(batch),
                                        _ptr(ids), _ptr(scores), C.byref(st)))

@@ -205,7 +205,7 @@ void leann_destroy(leann_ctx *ctx)
     (void)hipStreamSynchronize(ctx->stream);
     DevBuf *bufs[] = {&ctx->w_bf16, &ctx->w_f32, &ctx->x, &ctx->qkv, &ctx->att, &ctx->pre, &ctx->hid, &ctx->cu,
                       &ctx->len, &ctx->meta, &ctx->enc_ids, &ctx->s_state, &ctx->s_emb, &ctx->s_lut, &ctx->s_seen,
-                      &ctx->s_misc, &ctx->s_owner};
+                      &ctx->s_misc, &ctx->s_owner, &ctx->s_buf};
     for (DevBuf *b : bufs) b->release();
     ctx->prof_tokens.release();
     for (auto &sp : ctx->prof_spans) {
@@ -315,6 +315,15 @@ int leann_search(leann_ctx *ctx, const float *queries_dev, int64_t nq, const lea
                  const leann_chunks *chunks, const leann_emb_cache *cache, int32_t ef, int32_t k, float rerank_ratio,
                  int32_t batch, int64_t *out_ids_dev, float *out_scores_dev, leann_search_stats *stats_host)
 {
+    return leann_search_updates(ctx, queries_dev, nq, graph, pq, chunks, cache, nullptr, ef, k, rerank_ratio, batch,
+                                out_ids_dev, out_scores_dev, stats_host);
+}
+
+int leann_search_updates(leann_ctx *ctx, const float *queries_dev, int64_t nq, const leann_graph *graph,
+                         const leann_pq *pq, const leann_chunks *chunks, const leann_emb_cache *cache,
+                         const leann_updates *updates, int32_t ef, int32_t k, float rerank_ratio, int32_t batch,
+                         int64_t *out_ids_dev, float *out_scores_dev, leann_search_stats *stats_host)
+{
     if (!ctx || !graph || !pq || nq < 0 || (nq > 0 && (!queries_dev || !out_ids_dev || !out_scores_dev))) {
         leann_set_error("leann_search: null argument or negative query count");
         return LEANN_EINVAL;
@@ -337,10 +346,15 @@ int leann_search(leann_ctx *ctx, const float *queries_dev, int64_t nq, const lea
         leann_set_error("leann_search: embedding cache with null pointers");
         return LEANN_EINVAL;
     }
+    if (updates && (updates->buffer_n < 0 || updates->buffer_n > (1 << 24) ||
+                    (updates->buffer_n > 0 && (!updates->buffer_emb || !updates->buffer_ids)))) {
+        leann_set_error("leann_search: add buffer with null pointers or a row count outside 0..2^24");
+        return LEANN_EINVAL;
+    }
     if (stats_host) *stats_host = leann_search_stats{};
     if (nq == 0) return LEANN_OK;
     LEANN_HIP(hipSetDevice(ctx->device));
-    return search_run(ctx, queries_dev, nq, graph, pq, chunks, cache, ef, k, rerank_ratio, batch, out_ids_dev,
+    return search_run(ctx, queries_dev, nq, graph, pq, chunks, cache, updates, ef, k, rerank_ratio, batch, out_ids_dev,
                       out_scores_dev, stats_host);
 }
 

@@ -62,7 +62,7 @@ struct leann_ctx {
     // encoder workspace
     DevBuf x, qkv, att, pre, hid, cu, len, meta, enc_ids;
     // search workspace
-    DevBuf s_state, s_emb, s_lut, s_seen, s_misc, s_owner;
+    DevBuf s_state, s_emb, s_lut, s_seen, s_misc, s_owner, s_buf;
     // optional per-kernel timing (leann_profile_begin / leann_profile_end)
     bool prof_on = false;
     DevBuf prof_tokens;  // device int64: valid tokens sent through the encoder while profiling
@@ -102,5 +102,5 @@ int pq_build_lut(leann_ctx *ctx, const float *queries_dev, int64_t nq, const lea
 
 // ---- search.hip
 int search_run(leann_ctx *ctx, const float *queries_dev, int64_t nq, const leann_graph *graph, const leann_pq *pq,
-               const leann_chunks *chunks, const leann_emb_cache *cache, int32_t ef, int32_t k, float alpha,
+               const leann_chunks *chunks, const leann_emb_cache *cache, const leann_updates *upd, int32_t ef, int32_t k, float alpha,
                int32_t batch, int64_t *out_ids_dev, float *out_scores_dev, leann_search_stats *stats);

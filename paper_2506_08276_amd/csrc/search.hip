@@ -392,45 +392,69 @@ __global__ __launch_bounds__(64) void score_insert_kernel(SearchState s, const f
     }
 }
 
-// k best of EQ -> outputs, padded with id -1 / score -inf.  One wavefront per query.
-__global__ __launch_bounds__(64) void finalize_kernel(SearchState s, int k, int64_t *__restrict__ out_ids,
-                                                      float *__restrict__ out_scores)
+// Exact scores of the add buffer (App. B "Batched Add Operation": buffered chunks are scanned, not traversed):
+// out[q][r] = <queries[q], buf[r]>.  One wavefront per (query, buffer row).
+__global__ __launch_bounds__(256) void buffer_score_kernel(const float *__restrict__ queries, const float *__restrict__ buf,
+                                                           int nb, int d, float *__restrict__ out)
+{
+    const int q = blockIdx.y, r = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (r >= nb) return;
+    const float *qv = queries + (size_t)q * d, *e = buf + (size_t)r * d;
+    float acc = 0.f;
+    for (int i = lane; i < d; i += 64) acc += qv[i] * e[i];
+    for (int o = 32; o; o >>= 1) acc += __shfl_xor(acc, o, 64);
+    if (lane == 0) out[(size_t)q * nb + r] = acc;
+}
+
+// Output stage: the k best of (EQ without soft-deleted nodes) united with the scored add buffer, under
+// (score desc, id asc); padded with id -1 / score -inf.  One wavefront per query; position p < n_eq is an EQ
+// entry, p >= n_eq a buffer row.  Ids are unique over both, so "strictly after the last one emitted" selects the
+// next.
+__global__ __launch_bounds__(64) void finalize_kernel(SearchState s, int k, const uint32_t *__restrict__ deleted_bits,
+                                                      const float *__restrict__ buf_scores,
+                                                      const uint32_t *__restrict__ buf_ids, int nb,
+                                                      int64_t *__restrict__ out_ids, float *__restrict__ out_scores)
 {
     const int q = blockIdx.x, lane = threadIdx.x;
     const int n_eq = s.eq_n[q];
     const float *eqs = s.eq_score + (size_t)q * s.ef;
     const uint32_t *eqi = s.eq_id + (size_t)q * s.ef;
+    const float *bsc = buf_scores + (size_t)q * nb;
     float last_s = INFINITY;
     uint32_t last_id = 0;
-    bool have_last = false;
+    bool have_last = false, exhausted = false;
     for (int j = 0; j < k; ++j) {
         float bs = -INFINITY;
         uint32_t bid = 0xffffffffu;
         int bpos = -1;
-        for (int i = lane; i < n_eq; i += 64) {
-            const float x = eqs[i];
-            const uint32_t id = eqi[i];
-            if (have_last && !better(last_s, last_id, x, id)) continue;  // already emitted (ids are unique)
-            if (bpos < 0 || better(x, id, bs, bid)) {
-                bs = x;
-                bid = id;
-                bpos = i;
+        if (!exhausted)
+            for (int i = lane; i < n_eq + nb; i += 64) {
+                float x;
+                uint32_t id;
+                if (i < n_eq) {
+                    x = eqs[i];
+                    id = eqi[i];
+                    if (deleted_bits && (deleted_bits[id >> 5] >> (id & 31) & 1u)) continue;
+                } else {
+                    x = bsc[i - n_eq];
+                    id = buf_ids[i - n_eq];
+                }
+                if (have_last && !better(last_s, last_id, x, id)) continue;  // already emitted
+                if (bpos < 0 || better(x, id, bs, bid)) {
+                    bs = x;
+                    bid = id;
+                    bpos = i;
+                }
             }
-        }
         wave_best(bs, bid, bpos);
         if (lane == 0) {
             out_ids[(size_t)q * k + j] = bpos >= 0 ? (int64_t)bid : -1;
             out_scores[(size_t)q * k + j] = bpos >= 0 ? bs : -INFINITY;
         }
-        if (bpos < 0) {
-            have_last = true;
-            last_s = -INFINITY;
-            last_id = 0;  // nothing is strictly after (-inf, 0) except nothing: stays empty
-        } else {
-            have_last = true;
-            last_s = bs;
-            last_id = bid;
-        }
+        if (bpos < 0) exhausted = true;
+        have_last = true;
+        last_s = bs;
+        last_id = bid;
     }
 }
 
@@ -439,8 +463,8 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 }  // namespace
 
 int search_run(leann_ctx *ctx, const float *queries_dev, int64_t nq, const leann_graph *graph, const leann_pq *pq,
-               const leann_chunks *chunks, const leann_emb_cache *cache, int32_t ef, int32_t k, float alpha, int32_t batch,
-               int64_t *out_ids_dev, float *out_scores_dev, leann_search_stats *stats)
+               const leann_chunks *chunks, const leann_emb_cache *cache, const leann_updates *upd, int32_t ef, int32_t k,
+               float alpha, int32_t batch, int64_t *out_ids_dev, float *out_scores_dev, leann_search_stats *stats)
 {
     const int d = ctx->desc.hidden, m_sub = pq->m_sub;
     const int64_t n = graph->n;
@@ -588,7 +612,21 @@ int search_run(leann_ctx *ctx, const float *queries_dev, int64_t nq, const leann
             ++rounds;
         }
         if (rc != LEANN_OK) break;
-        hipLaunchKernelGGL(finalize_kernel, dim3(g), dim3(64), 0, st, s, k, out_ids_dev + (size_t)q0 * k,
+        const int nb = upd ? (int)upd->buffer_n : 0;
+        const float *buf_scores = nullptr;
+        if (nb > 0) {
+            if ((size_t)g * nb * sizeof(float) > ((size_t)4 << 30)) {
+                leann_set_error("leann_search: %d queries x %d buffered rows exceed the 4 GiB score workspace", g, nb);
+                rc = LEANN_ECAPACITY;
+                break;
+            }
+            LEANN_TRY(ctx->s_buf.reserve((size_t)g * nb * sizeof(float)));
+            buf_scores = (const float *)ctx->s_buf.p;
+            hipLaunchKernelGGL(buffer_score_kernel, dim3((nb + 3) / 4, g), dim3(256), 0, st, queries_dev + (size_t)q0 * d,
+                               upd->buffer_emb, nb, d, (float *)ctx->s_buf.p);
+        }
+        hipLaunchKernelGGL(finalize_kernel, dim3(g), dim3(64), 0, st, s, k, upd ? upd->deleted_bits : nullptr, buf_scores,
+                           upd ? upd->buffer_ids : nullptr, nb, out_ids_dev + (size_t)q0 * k,
                            out_scores_dev + (size_t)q0 * k);
     }
     if (rc == LEANN_OK) rc = mark();

@@ -105,6 +105,52 @@ def test_hub_embedding_cache_changes_work_not_results(L, world):
           f"{st0['encoded_chunks']} -> {st1['encoded_chunks']}")
 
 
+def pack_bits(flags):
+    """uint8 flags [n] -> int32 words, bit (v & 31) of word (v >> 5)."""
+    n = len(flags)
+    padded = np.zeros((n + 31) // 32 * 32, np.uint8)
+    padded[:n] = flags
+    return np.packbits(padded.reshape(-1, 32), axis=1, bitorder="little").view(np.uint32).reshape(-1).view(np.int32)
+
+
+@pytest.mark.parametrize("ef,k,alpha,batch", [(32, 3, 0.2, 32), (16, 8, 1.0, 1), (64, 10, 0.05, 7)])
+def test_pending_updates_against_oracle(L, orc, world, ef, k, alpha, batch):
+    """Soft-delete flags and the add buffer (App. B) on the exact-logic setting: stored fp32 oracle embeddings for
+    every node, so ids must be identical and scores agree to summation order."""
+    w = world
+    rng = np.random.default_rng(5)
+    n, d = w["n"], w["emb"].shape[1]
+    deleted = (rng.random(n) < 0.15).astype(np.uint8)
+    nb = 37
+    buf_ids = np.arange(n, n + nb, dtype=np.int64)
+    near = w["queries"][rng.integers(0, len(w["queries"]), 10)] + 0.05 * rng.standard_normal((10, d)).astype(np.float32)
+    buf = np.concatenate([near, rng.standard_normal((nb - 10, d))]).astype(np.float32)
+    buf /= np.linalg.norm(buf, axis=1, keepdims=True)
+    say(f"updates ef={ef} k={k} alpha={alpha} batch={batch}: {int(deleted.sum())} deleted, {nb} buffered")
+    for use_del, use_buf in ((True, False), (False, True), (True, True)):
+        ids, scores, st = L.leann_search_updates(
+            w["ctx"], w["q"], w["graph"], w["pq"], w["t"], w["l"], ef, k, alpha, batch, cache=w["full_cache"],
+            deleted_bits=to_dev(pack_bits(deleted)) if use_del else None,
+            buffer=(to_dev(buf_ids.astype(np.uint32).view(np.int32)), to_dev(buf)) if use_buf else None)
+        ids, scores = ids.cpu().numpy(), scores.cpu().numpy()
+        hops = 0
+        for qi, q in enumerate(w["queries"]):
+            r = orc.search_table(q, w["row_ptr"], w["col_idx"], w["entry"], w["cb"], w["codes"], w["emb"], ef, k, alpha,
+                                 batch, deleted=deleted if use_del else None, buffer=(buf_ids, buf) if use_buf else None)
+            assert list(ids[qi]) == list(r["ids"]), (use_del, use_buf, qi, ids[qi], r["ids"])
+            np.testing.assert_allclose(scores[qi], r["scores"], atol=2e-6)
+            if use_del:
+                assert not any(deleted[i] for i in ids[qi] if 0 <= i < n)
+            hops += r["stats"]["hops"]
+        assert st["hops"] == hops  # the traversal is that of the plain search
+    # no updates through the same entry point = leann_search
+    a = L.leann_search_updates(w["ctx"], w["q"], w["graph"], w["pq"], w["t"], w["l"], ef, k, alpha, batch,
+                               cache=w["full_cache"])
+    b = L.leann_search(w["ctx"], w["q"], w["graph"], w["pq"], w["t"], w["l"], ef, k, alpha, batch, cache=w["full_cache"])
+    import torch
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
 def decided_ranks(log_scores, k, gap=1e-3):
     """Ranks (0-based) of the oracle's top-k whose score is more than `gap` away from both neighbours in the
     oracle's sorted list of exact scores: there the id is decided by more than the precision difference."""
