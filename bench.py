@@ -124,7 +124,7 @@ def encoder_only(args):
     import leann_inputs as li
     import paper_2506_08276_amd as L
     L.load_library()
-    cfg = dict(li.BASE)
+    cfg = dict(li.SMALL if args.shape == "small" else li.BASE)
     w = li.encoder_weights(cfg, li.config_seed(2), bf16_exact=True)
     ctx = L.leann_create(cfg, torch.from_numpy(w).to("cuda:0").to(torch.bfloat16))
     if args.max_tokens:
@@ -135,7 +135,7 @@ def encoder_only(args):
     dst.copy_(src)
     torch.cuda.synchronize()
     L.leann_destroy(ctx)
-    print(json.dumps({"mode": "encoder-only", "encoder": res, "calibration_copy_bytes": int(src.numel() * 4)}), flush=True)
+    print(json.dumps({"mode": "encoder-only", "shape": args.shape, "encoder": res, "calibration_copy_bytes": int(src.numel() * 4)}), flush=True)
 
 
 def adc_microbench(args):
@@ -252,6 +252,8 @@ def main():
                     help="extra leg: store the embeddings of this fraction of the nodes (highest degree); 0 = skip")
     ap.add_argument("--max-tokens", type=int, default=0, help="padded tokens per encoder pass (0 = library default)")
     ap.add_argument("--encoder-only", action="store_true", help="run only the seq-256 encoder batches (profiling aid)")
+    ap.add_argument("--shape", choices=["base", "small"], default="base",
+                    help="with --encoder-only: BERT-base shape (12 x 768) or the 34 M-parameter 12 x 384 encoder")
     ap.add_argument("--profile-pass", action="store_true", help="with --encoder-only: a single 2048-chunk batch")
     ap.add_argument("--adc-microbench", action="store_true", help="run only the stand-alone ADC scorer table")
     ap.add_argument("--no-cpu-baseline", action="store_true")

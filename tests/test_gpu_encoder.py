@@ -120,3 +120,28 @@ def test_base_shape_sample_matches_oracle(L, orc):
     assert np.abs(got[ids] - want_bf).max() <= TOL_BF16_MODE
     print("base sample max-abs vs fp32 oracle %.3e, vs bf16-mode oracle %.3e" %
           (np.abs(got[ids] - want).max(), np.abs(got[ids] - want_bf).max()))
+
+
+def test_small_shape_sample_matches_oracle(L, orc):
+    """The 12 x 384 encoder (second throughput point; widths that are not multiples of 256 take the 128-wide GEMM
+    tile) at seq 256; a few chunks against the oracle."""
+    import torch
+    cfg = li.SMALL
+    say("small-shape sample (12 x 384)")
+    w = li.encoder_weights(cfg, li.config_seed(2) + 7, bf16_exact=True)
+    tokens, lengths = li.uniform_chunks(300, 256, 1, cfg["vocab"], 64, 256, li.config_seed(2) + 8)
+    lengths[:4] = [1, 47, 129, 256]
+    ctx = L.leann_create(cfg, to_dev(w).to(torch.bfloat16))
+    try:
+        got = L.leann_embed(ctx, to_dev(tokens), to_dev(lengths), hidden=384).cpu().numpy()
+    finally:
+        L.leann_destroy(ctx)
+    ids = np.array([0, 1, 2, 3, 150, 299], np.int64)
+    e = orc.desc(**cfg)
+    want = orc.embed(e, w, tokens, lengths, ids=ids)
+    want_bf = orc.embed(e, w, tokens, lengths, ids=ids, precision=1)
+    assert np.isfinite(got).all()
+    assert np.abs(got[ids] - want).max() <= TOL_FP32
+    assert np.abs(got[ids] - want_bf).max() <= TOL_BF16_MODE
+    print("small sample max-abs vs fp32 oracle %.3e, vs bf16-mode oracle %.3e" %
+          (np.abs(got[ids] - want).max(), np.abs(got[ids] - want_bf).max()))
