@@ -797,3 +797,228 @@ int orc_search_encoder(const float *q, const uint64_t *row_ptr, const uint32_t *
     return orc_search(q, e->hidden, row_ptr, col_idx, n, entry, codebook, codes, m_sub, embed_from_encoder, &u, ef,
                       k, alpha, batch, alpha_mode, out_ids, out_scores, stats, NULL, NULL, 0, NULL, NULL, 0, NULL);
 }
+
+/* ------------------------------------------------------------------ */
+/* C4. graph construction (Algorithm 3 and the node-insertion listing   */
+/*     of the update appendix)                                          */
+/* ------------------------------------------------------------------ */
+
+/*
+ * The index graph is built by inserting the nodes one after the other
+ * (Algorithm 3, "for v in V(G)").  For node v:
+ *   W   <- Search(v, efC): Algorithm 1 on the graph built so far, exact
+ *          similarities <e_v, e_x> from the stored embeddings (they exist while
+ *          the index is built), queue length efC;
+ *   R   <- Shrink(W, M0): walk W by ascending distance to v and keep x unless a
+ *          kept y is closer to x than v is (the RNG rule of the appendix:
+ *          Dist(x, y) < Dist(x, v)); stop at M0 kept.  M0 = M for the nodes
+ *          flagged as high-degree, m for the others (Algorithm 3);
+ *   add the edges v -> r and r -> v for r in R;
+ *   a neighbour r whose list now exceeds M is shrunk to M with the same rule,
+ *   anchored at r ("allow all nodes to form bidirectional links ... up to the
+ *   higher threshold M").
+ * Similarity = inner product of the (unit-norm) embeddings, so "closer" =
+ * larger similarity; total order (similarity descending, id ascending).
+ *
+ * Readings where the text is silent:
+ *  - insertion order = id order; the search of an insertion starts at node 0
+ *    (the first node inserted);
+ *  - a list that does not exceed its cap is kept as it is (no RNG pass);
+ *  - batch > 1 is a batch-synchronous generalisation: the nodes of a batch
+ *    search the graph as it was before the batch, then their edges are committed
+ *    in id order and every neighbour that received edges is shrunk once, at the
+ *    end of the batch.  Batch k holds min(batch, max(1, inserted / ramp)) nodes.
+ *    batch = 1 is the listing itself.
+ */
+
+typedef struct {
+    int32_t *adj; /* [n][cap] */
+    int32_t *deg; /* [n] */
+    int32_t cap;
+} build_graph;
+
+static float simf(const float *emb, int32_t d, int64_t a, int64_t b)
+{
+    float s = 0.f;
+    for (int i = 0; i < d; ++i) s += emb[a * d + i] * emb[b * d + i];
+    return s;
+}
+
+/* Shrink: ids[0..cnt) with similarities sim[] to the anchor; keeps at most cap, writes them (best first) to out. */
+static int shrink_rng(const float *emb, int32_t d, const int32_t *ids, const float *sim, int cnt, int cap,
+                      int32_t *out, uint8_t *taken /* scratch [cnt] */)
+{
+    int kept = 0;
+    memset(taken, 0, (size_t)cnt);
+    for (int step = 0; step < cnt && kept < cap; ++step) {
+        int b = -1;
+        for (int i = 0; i < cnt; ++i)
+            if (!taken[i] && (b < 0 || better(sim[i], ids[i], sim[b], ids[b]))) b = i;
+        taken[b] = 1;
+        int ok = 1;
+        for (int j = 0; j < kept && ok; ++j)
+            if (simf(emb, d, ids[b], out[j]) > sim[b]) ok = 0; /* a kept node is closer to x than the anchor is */
+        if (ok) out[kept++] = ids[b];
+    }
+    return kept;
+}
+
+/* Algorithm 1 on the build graph with exact similarities to node v; fills w_ids / w_sim (unsorted), returns count. */
+static int build_search(const float *emb, int32_t d, const build_graph *g, int64_t n_inserted, int64_t v, int efC,
+                        int32_t *w_ids, float *w_sim, uint8_t *w_vis, uint8_t *seen /* [n], zero on entry and exit */,
+                        int32_t *touched)
+{
+    if (n_inserted == 0) return 0;
+    int n_w = 0, n_touched = 0;
+    w_ids[0] = 0; w_sim[0] = simf(emb, d, v, 0); w_vis[0] = 0; n_w = 1;
+    seen[0] = 1; touched[n_touched++] = 0;
+    for (;;) {
+        int u = -1;
+        for (int i = 0; i < n_w; ++i)
+            if (!w_vis[i] && (u < 0 || better(w_sim[i], w_ids[i], w_sim[u], w_ids[u]))) u = i;
+        if (u < 0) break;
+        w_vis[u] = 1;
+        const int32_t un = w_ids[u];
+        for (int e = 0; e < g->deg[un]; ++e) {
+            const int32_t x = g->adj[(int64_t)un * g->cap + e];
+            if (seen[x]) continue;
+            seen[x] = 1; touched[n_touched++] = x;
+            const float s = simf(emb, d, v, x);
+            if (n_w < efC) {
+                w_ids[n_w] = x; w_sim[n_w] = s; w_vis[n_w] = 0; ++n_w;
+            } else {
+                int worst = 0;
+                for (int i = 1; i < n_w; ++i)
+                    if (better(w_sim[worst], w_ids[worst], w_sim[i], w_ids[i])) worst = i;
+                if (better(s, x, w_sim[worst], w_ids[worst])) { w_ids[worst] = x; w_sim[worst] = s; w_vis[worst] = 0; }
+            }
+        }
+    }
+    for (int i = 0; i < n_touched; ++i) seen[touched[i]] = 0;
+    return n_w;
+}
+
+/*
+ * emb[n][d]; is_hub[n] (NULL: every node may keep M edges); out: CSR with
+ * row_ptr[n+1] and col_idx (capacity n * M).  Returns the number of edges in
+ * *n_edges.  searched_total (optional): sum of |W| over all insertions.
+ */
+int orc_build_graph(const float *emb, int64_t n, int32_t d, const uint8_t *is_hub, int32_t efC, int32_t M, int32_t m,
+                    int32_t batch, int32_t ramp, uint64_t *row_ptr, uint32_t *col_idx, int64_t *n_edges,
+                    int64_t *searched_total)
+{
+    if (!emb || !row_ptr || !col_idx || n < 1 || d < 1 || efC < 1 || M < 1 || m < 1 || m > M || batch < 1 || ramp < 1)
+        return ORC_EINVAL;
+    const int cap = M + batch; /* a list can grow by one edge per node of a batch before it is shrunk */
+    build_graph g = {calloc((size_t)n * cap, sizeof(int32_t)), calloc((size_t)n, sizeof(int32_t)), cap};
+    int32_t *fwd = malloc(sizeof(int32_t) * (size_t)batch * M);
+    int32_t *fwd_n = malloc(sizeof(int32_t) * (size_t)batch);
+    int32_t *w_ids = malloc(sizeof(int32_t) * (size_t)efC);
+    float *w_sim = malloc(sizeof(float) * (size_t)efC);
+    uint8_t *w_vis = malloc((size_t)efC);
+    uint8_t *seen = calloc((size_t)n, 1);
+    int32_t *touched = malloc(sizeof(int32_t) * (size_t)n);
+    uint8_t *got = calloc((size_t)n, 1);
+    const int tmp_n = (cap > efC ? cap : efC) + 1;
+    int32_t *tmp_ids = malloc(sizeof(int32_t) * (size_t)tmp_n);
+    float *tmp_sim = malloc(sizeof(float) * (size_t)tmp_n);
+    uint8_t *taken = malloc((size_t)tmp_n);
+    int rc = ORC_OK;
+    int64_t searched = 0;
+    if (!g.adj || !g.deg || !fwd || !fwd_n || !w_ids || !w_sim || !w_vis || !seen || !touched || !got || !tmp_ids ||
+        !tmp_sim || !taken) {
+        rc = ORC_ENOMEM;
+        goto out;
+    }
+    for (int64_t s = 0; s < n;) {
+        int64_t b = s / ramp;
+        if (b < 1) b = 1;
+        if (b > batch) b = batch;
+        if (s + b > n) b = n - s;
+        /* searches and neighbour selection on the graph as it is before the batch */
+        for (int64_t i = 0; i < b; ++i) {
+            const int64_t v = s + i;
+            const int n_w = build_search(emb, d, &g, s, v, efC, w_ids, w_sim, w_vis, seen, touched);
+            searched += n_w;
+            const int cap_v = (!is_hub || is_hub[v]) ? M : m;
+            fwd_n[i] = shrink_rng(emb, d, w_ids, w_sim, n_w, cap_v, fwd + i * M, taken);
+        }
+        /* commit in id order: forward lists, then reverse edges */
+        for (int64_t i = 0; i < b; ++i) {
+            const int64_t v = s + i;
+            for (int j = 0; j < fwd_n[i]; ++j) g.adj[v * cap + j] = fwd[i * M + j];
+            g.deg[v] = fwd_n[i];
+        }
+        for (int64_t i = 0; i < b; ++i) {
+            const int64_t v = s + i;
+            for (int j = 0; j < fwd_n[i]; ++j) {
+                const int32_t r = fwd[i * M + j];
+                g.adj[(int64_t)r * cap + g.deg[r]++] = (int32_t)v;
+                got[r] = 1;
+            }
+        }
+        /* neighbours that received edges: back under the cap M */
+        for (int64_t i = 0; i < b; ++i)
+            for (int j = 0; j < fwd_n[i]; ++j) {
+                const int32_t r = fwd[i * M + j];
+                if (!got[r]) continue;
+                got[r] = 0;
+                if (g.deg[r] <= M) continue;
+                const int cnt = g.deg[r];
+                for (int e = 0; e < cnt; ++e) {
+                    tmp_ids[e] = g.adj[(int64_t)r * cap + e];
+                    tmp_sim[e] = simf(emb, d, r, tmp_ids[e]);
+                }
+                g.deg[r] = shrink_rng(emb, d, tmp_ids, tmp_sim, cnt, M, g.adj + (int64_t)r * cap, taken);
+            }
+        s += b;
+    }
+    {
+        int64_t e = 0;
+        for (int64_t v = 0; v < n; ++v) {
+            row_ptr[v] = (uint64_t)e;
+            for (int j = 0; j < g.deg[v]; ++j) col_idx[e++] = (uint32_t)g.adj[v * cap + j];
+        }
+        row_ptr[n] = (uint64_t)e;
+        if (n_edges) *n_edges = e;
+    }
+    if (searched_total) *searched_total = searched;
+out:
+    free(g.adj); free(g.deg); free(fwd); free(fwd_n); free(w_ids); free(w_sim); free(w_vis); free(seen); free(touched);
+    free(got); free(tmp_ids); free(tmp_sim); free(taken);
+    return rc;
+}
+
+/* Algorithm 3, "nodes with the top beta% highest degrees": the ceil(beta * n) nodes of largest out-degree in a CSR
+ * graph, ties to the lower id.  is_hub[n] receives 0 / 1. */
+int orc_top_degree(const uint64_t *row_ptr, int64_t n, double beta, uint8_t *is_hub)
+{
+    if (!row_ptr || !is_hub || n < 1 || !(beta >= 0.0) || beta > 1.0) return ORC_EINVAL;
+    int64_t want = (int64_t)ceil(beta * (double)n);
+    if (want > n) want = n;
+    memset(is_hub, 0, (size_t)n);
+    for (int64_t c = 0; c < want; ++c) { /* selection by repeated maximum: quadratic, plain */
+        int64_t b = -1;
+        for (int64_t v = 0; v < n; ++v) {
+            if (is_hub[v]) continue;
+            const int64_t dv = (int64_t)(row_ptr[v + 1] - row_ptr[v]);
+            if (b < 0 || dv > (int64_t)(row_ptr[b + 1] - row_ptr[b])) b = v;
+        }
+        is_hub[b] = 1;
+    }
+    return ORC_OK;
+}
+
+/* Shrink alone (for its pins): candidates ids[cnt] around anchor node a of emb; out gets at most cap ids, best first. */
+int orc_shrink(const float *emb, int64_t n, int32_t d, int64_t anchor, const int32_t *ids, int32_t cnt, int32_t cap,
+               int32_t *out, int32_t *n_out)
+{
+    if (!emb || !ids || !out || !n_out || cnt < 0 || cap < 1 || anchor < 0 || anchor >= n) return ORC_EINVAL;
+    float *sim = malloc(sizeof(float) * (size_t)(cnt + 1));
+    uint8_t *taken = malloc((size_t)cnt + 1);
+    if (!sim || !taken) { free(sim); free(taken); return ORC_ENOMEM; }
+    for (int i = 0; i < cnt; ++i) sim[i] = simf(emb, d, anchor, ids[i]);
+    *n_out = shrink_rng(emb, d, ids, sim, cnt, cap, out, taken);
+    free(sim); free(taken);
+    return ORC_OK;
+}

@@ -16,7 +16,7 @@ _lib = None
 
 __all__ = [
     "build", "EncoderDesc", "desc", "weight_count", "embed", "permutation", "pq_train", "pq_encode", "pq_decode",
-    "lut", "adc", "exact_topk", "search_table", "search_encoder", "search_callback",
+    "lut", "adc", "exact_topk", "search_table", "search_encoder", "search_callback", "build_graph", "top_degree", "shrink",
 ]
 
 
@@ -299,3 +299,43 @@ def search_encoder(q, row_ptr, col_idx, entry, codebook, codes, e, weights, toke
     return {"ids": out_ids, "scores": out_sc,
             "stats": {"hops": st.hops, "adc_candidates": st.adc_candidates, "recomputed": st.recomputed,
                       "flushes": st.flushes}}
+
+
+def build_graph(emb, efC, M, m=None, is_hub=None, batch=1, ramp=1):
+    """Algorithm 3: graph construction by insertion with RNG neighbour selection; nodes flagged in is_hub (uint8 [n],
+    None = all) may keep M forward edges, the others m.  Returns (row_ptr uint64 [n+1], col_idx uint32 [E], stats)."""
+    emb = _f32(emb)
+    n, d = emb.shape
+    m = M if m is None else m
+    if is_hub is not None:
+        is_hub = np.ascontiguousarray(is_hub, dtype=np.uint8)
+        assert is_hub.shape == (n,)
+    row_ptr = np.empty(n + 1, dtype=np.uint64)
+    col_idx = np.empty(n * M, dtype=np.uint32)
+    n_edges, searched = C.c_int64(0), C.c_int64(0)
+    rc = _load().orc_build_graph(_p(emb, C.c_float), C.c_int64(n), C.c_int32(d), _p(is_hub, C.c_uint8), C.c_int32(efC),
+                                 C.c_int32(M), C.c_int32(m), C.c_int32(batch), C.c_int32(ramp), _p(row_ptr, C.c_uint64),
+                                 _p(col_idx, C.c_uint32), C.byref(n_edges), C.byref(searched))
+    _check(rc, "build_graph")
+    return row_ptr, col_idx[:n_edges.value].copy(), {"edges": n_edges.value, "searched": searched.value}
+
+
+def top_degree(row_ptr, beta):
+    """uint8 flags [n] of the ceil(beta * n) nodes of largest out-degree (ties: lower id)."""
+    row_ptr = np.ascontiguousarray(row_ptr, dtype=np.uint64)
+    n = len(row_ptr) - 1
+    out = np.empty(n, dtype=np.uint8)
+    _check(_load().orc_top_degree(_p(row_ptr, C.c_uint64), C.c_int64(n), C.c_double(beta), _p(out, C.c_uint8)), "top_degree")
+    return out
+
+
+def shrink(emb, anchor, ids, cap):
+    """RNG neighbour selection around node `anchor` among candidate node ids; returns the kept ids, best first."""
+    emb = _f32(emb)
+    ids = np.ascontiguousarray(ids, dtype=np.int32)
+    out = np.empty(max(cap, 1), dtype=np.int32)
+    n_out = C.c_int32(0)
+    _check(_load().orc_shrink(_p(emb, C.c_float), C.c_int64(emb.shape[0]), C.c_int32(emb.shape[1]), C.c_int64(anchor),
+                              _p(ids, C.c_int32), C.c_int32(len(ids)), C.c_int32(cap), _p(out, C.c_int32),
+                              C.byref(n_out)), "shrink")
+    return out[:n_out.value].copy()
