@@ -210,6 +210,35 @@ int leann_search_updates(leann_ctx *ctx, const float *queries_dev, int64_t nq, c
                          const leann_updates *updates, int32_t ef, int32_t k, float rerank_ratio, int32_t batch,
                          int64_t *out_ids_dev, float *out_scores_dev, leann_search_stats *stats_host);
 
+/*
+ * Index graph construction by insertion (Algorithm 3 with the node-insertion listing of
+ * the update appendix).  Nodes enter in id order.  For node v: W = best-first search
+ * (Algorithm 1, exact similarities <e_v, e_x> from emb, queue length efC, start at node 0)
+ * on the graph built so far; neighbours = RNG selection from W (walk by descending
+ * similarity, keep x unless a kept y has <e_x, e_y> > <e_x, e_v>), at most M for nodes
+ * flagged in is_hub (NULL: every node), m for the others; edges are added in both
+ * directions, and a neighbour whose list exceeds M is shrunk to M with the same rule.
+ * Total order (similarity descending, id ascending).
+ * batch > 1: the nodes of a batch search the graph as it was before the batch (one
+ * wavefront each), then their edges are committed in id order and every node that
+ * received edges is shrunk once; batch k holds min(batch, max(1, inserted / ramp)) nodes.
+ * batch = 1 is the sequential listing.
+ *   emb_dev fp32[n][d] (device); is_hub_dev uint8[n] or NULL (device);
+ *   row_ptr_dev uint64[n + 1], col_idx_dev uint32 with room for n * M entries (device,
+ *   caller-owned); n_edges_host receives the edge count.  Scratch is allocated and freed
+ *   inside the call (n * (M + batch) * 4 + batch * n * 2 bytes).  Synchronises the stream.
+ * Errors: efC outside 1..256, M outside 1..64, m outside 1..M, batch outside 1..256,
+ * ramp < 1, n >= 2^31 -> LEANN_EINVAL.
+ */
+int leann_build_graph(leann_ctx *ctx, const float *emb_dev, int64_t n, int32_t d, const uint8_t *is_hub_dev,
+                      int32_t efC, int32_t M, int32_t m, int32_t batch, int32_t ramp, uint64_t *row_ptr_dev,
+                      uint32_t *col_idx_dev, int64_t *n_edges_host);
+
+/* Algorithm 3, "nodes with the top beta% highest degrees": is_hub_dev[v] = 1 for the
+ * ceil(beta * n) nodes of largest out-degree in the CSR graph (ties: lower id), else 0.
+ * Degrees above 4096 -> LEANN_ECAPACITY. */
+int leann_top_degree(leann_ctx *ctx, const uint64_t *row_ptr_dev, int64_t n, double beta, uint8_t *is_hub_dev);
+
 /* Tuning knobs (all optional): largest number of tokens one encoder pass holds
  * (workspace size), and the per-query capacity of the approximate queue. */
 int leann_set_limits(leann_ctx *ctx, int64_t max_tokens_per_pass, int32_t aq_capacity);

@@ -20,7 +20,7 @@ STATUS = {0: "LEANN_OK", -1: "LEANN_EINVAL", -2: "LEANN_ENOMEM", -3: "LEANN_EDEV
           -5: "LEANN_ECAPACITY"}
 EXPORTS = ["leann_last_error", "leann_create", "leann_destroy", "leann_embed", "leann_build_pq", "leann_pq_export",
            "leann_pq_import", "leann_pq_wrap", "leann_pq_info", "leann_pq_free", "leann_adc", "leann_search",
-           "leann_search_updates",
+           "leann_search_updates", "leann_build_graph", "leann_top_degree",
            "leann_set_limits", "leann_profile_begin", "leann_profile_end"]
 PROF_KINDS = ["gemm_qkv", "gemm_o", "gemm_ffn1", "gemm_ffn2", "attention", "layernorm", "enc_other", "traverse",
               "collect", "score_insert", "lut", "adc"]
@@ -258,6 +258,33 @@ def leann_search(ctx, queries, graph, pq, tokens, lengths, ef, k, rerank_ratio, 
                                        C.c_int32(ef), C.c_int32(k), C.c_float(rerank_ratio), C.c_int32(batch),
                                        _ptr(ids), _ptr(scores), C.byref(st)))
     return ids, scores, st.as_dict()
+
+
+def leann_build_graph(ctx, emb, efC, M, m=None, is_hub=None, batch=256, ramp=8):
+    """Algorithm 3 on the device.  emb float32 CUDA [n][d]; is_hub uint8 CUDA [n] or None.
+    Returns (row_ptr int64 CUDA tensor holding uint64 [n+1], col_idx int32 CUDA tensor holding uint32 [E])."""
+    _dev(emb, torch.float32, "emb")
+    n, d = emb.shape
+    m = M if m is None else m
+    if is_hub is not None:
+        _dev(is_hub, torch.uint8, "is_hub")
+        assert is_hub.numel() == n
+    row_ptr = torch.empty(n + 1, dtype=torch.int64, device=emb.device)
+    col_idx = torch.empty(n * M, dtype=torch.int32, device=emb.device)
+    edges = C.c_int64(0)
+    _check(load_library().leann_build_graph(ctx, _ptr(emb), C.c_int64(n), C.c_int32(d), _ptr(is_hub), C.c_int32(efC),
+                                            C.c_int32(M), C.c_int32(m), C.c_int32(batch), C.c_int32(ramp),
+                                            _ptr(row_ptr), _ptr(col_idx), C.byref(edges)))
+    return row_ptr, col_idx[:edges.value].clone()
+
+
+def leann_top_degree(ctx, row_ptr, beta):
+    """uint8 CUDA flags [n] of the ceil(beta * n) nodes of largest out-degree (ties: lower id)."""
+    _dev(row_ptr, torch.int64, "row_ptr")
+    n = row_ptr.numel() - 1
+    out = torch.empty(n, dtype=torch.uint8, device=row_ptr.device)
+    _check(load_library().leann_top_degree(ctx, _ptr(row_ptr), C.c_int64(n), C.c_double(beta), _ptr(out)))
+    return out
 
 
 def leann_profile_begin(ctx):
