@@ -202,6 +202,91 @@ def hub_cache_leg(L, torch, world, args, ef, qps_plain, ids_plain):
             "encoded_chunks_per_query": st["encoded_chunks"] / args.nq}
 
 
+def prune_ablation(args):
+    """--prune-ablation: Algorithm 3 on the device against the two naive ways to shrink a graph (Sec. 5, the ablation
+    on graph pruning): the original graph (every node may keep M edges), high-degree preserving pruning (top beta of
+    the nodes by degree keep M, the others m), a uniformly smaller degree cap with about the same number of edges, and
+    random removal of edges of the original graph down to the same count.  For each graph: recall@3 and recomputed
+    chunks per query over an ef sweep (two-level search of the bench, exact scores read from the stored embeddings so
+    the sweep costs no encoder time), and the first ef of the sweep that reaches the target recall."""
+    import numpy as np
+    import torch
+    import paper_2506_08276_amd as L
+    L.load_library()
+    world = build_world(args, L, torch)
+    ctx, emb, n = world["ctx"], world["emb"], args.n
+    dev = emb.device
+    M, m, beta, efC = args.prune_M, args.prune_m, 0.02, 2 * args.prune_M
+    cache = (torch.arange(n, dtype=torch.int32, device=dev), emb)
+
+    def timed_build(**kw):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        rp, ci = L.leann_build_graph(ctx, emb, efC, batch=1024, ramp=8, **kw)
+        torch.cuda.synchronize()
+        return rp, ci, time.perf_counter() - t0
+
+    def sweep(name, rp, ci, extra=None):
+        deg = (rp[1:] - rp[:-1]) + torch.bincount(ci.long(), minlength=n)
+        entry = int(torch.argmax(deg))  # highest total degree; torch.argmax returns the first maximum
+        rows = []
+        first = None
+        for ef in (16, 24, 32, 48, 64, 96, 128, 192, 256, 384):
+            ids, _, st = L.leann_search(ctx, world["queries"], (rp, ci, entry), world["pq"], world["t"], world["l"], ef,
+                                        args.k, args.rerank_ratio, args.batch, cache=cache)
+            rec = recall_at_3(ids, world["gt"])
+            rows.append({"ef": ef, "recall_at_3": rec, "recomputed_per_query": st["recomputed_chunks"] / args.nq})
+            if first is None and rec >= args.target_recall:
+                first = rows[-1]
+                break
+        out = {"mode": "prune-ablation", "graph": name, "edges": int(ci.numel()), "avg_degree": ci.numel() / n,
+               "graph_bytes": int(ci.numel()) * 4, "sweep": rows, "at_target": first}
+        if extra:
+            out.update(extra)
+        print(json.dumps(out), flush=True)
+        log(f"{name}: {ci.numel()} edges, target reached at {first}")
+        return out
+
+    rp0, ci0, t_orig = timed_build(M=M)
+    sweep(f"original (M={M})", rp0, ci0, {"build_s": t_orig, "build_nodes_per_s": n / t_orig})
+    is_hub = L.leann_top_degree(ctx, rp0, beta)
+    rp1, ci1, t_hub = timed_build(M=M, m=m, is_hub=is_hub)
+    target_edges = int(ci1.numel())
+    sweep(f"high-degree preserving (M={M}, m={m}, top {beta:.0%} keep M)", rp1, ci1,
+          {"build_s": t_hub, "build_nodes_per_s": n / t_hub})
+    # uniform smaller cap with about as many edges: the largest cap whose edge count does not exceed the target
+    best = None
+    for cap in range(m, M + 1):
+        rp, ci, t = timed_build(M=cap)
+        if ci.numel() > target_edges and best is not None:
+            break
+        best = (cap, rp, ci, t)
+        if ci.numel() > target_edges:
+            break
+    sweep(f"small M (M={best[0]})", best[1], best[2], {"build_s": best[3]})
+    # random removal of edges of the original graph down to the target count
+    g = torch.Generator(device="cpu").manual_seed(world["seed"] + 9)
+    keep = torch.zeros(ci0.numel(), dtype=torch.bool)
+    keep[torch.randperm(ci0.numel(), generator=g)[:target_edges]] = True
+    keep = keep.to(dev)
+    row_of = torch.repeat_interleave(torch.arange(n, device=dev), (rp0[1:] - rp0[:-1]))
+    cir = ci0[keep].contiguous()
+    rpr = torch.zeros(n + 1, dtype=torch.int64, device=dev)
+    rpr[1:] = torch.cumsum(torch.bincount(row_of[keep], minlength=n), 0)
+    sweep("random prune of the original", rpr, cir)
+    # the construction oracle on a prefix of the corpus, for scale (host cores: it is a sequential algorithm)
+    if not args.no_cpu_baseline:
+        sys.path.insert(0, ROOT)
+        import oracle
+        sample = emb[:1500].cpu().numpy()
+        t0 = time.perf_counter()
+        oracle.build_graph(sample, efC, M)
+        dt = time.perf_counter() - t0
+        print(json.dumps({"mode": "prune-ablation", "cpu_baseline": {"kind": "oracle", "value": len(sample) / dt,
+                          "unit": "nodes/s", "cores": 1, "sample": f"first {len(sample)} nodes of the corpus, efC={efC}, M={M}"}}),
+              flush=True)
+
+
 def cpu_baseline(world, recomputed_per_query, seconds_target=15.0):
     """The oracle as it stands, on a bounded sample of the same workload: oracle chunks/s over a few chunks per
     core, and queries/s derived as chunks/s / (recomputed chunks per query measured on the GPU run)."""
@@ -256,6 +341,9 @@ def main():
                     help="with --encoder-only: BERT-base shape (12 x 768) or the 34 M-parameter 12 x 384 encoder")
     ap.add_argument("--profile-pass", action="store_true", help="with --encoder-only: a single 2048-chunk batch")
     ap.add_argument("--adc-microbench", action="store_true", help="run only the stand-alone ADC scorer table")
+    ap.add_argument("--prune-ablation", action="store_true", help="graph construction variants: recall vs recomputation")
+    ap.add_argument("--prune-M", type=int, default=64)
+    ap.add_argument("--prune-m", type=int, default=16)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-encoder-bench", action="store_true")
     args = ap.parse_args()
@@ -267,6 +355,8 @@ def main():
         return encoder_only(args)
     if args.adc_microbench:
         return adc_microbench(args)
+    if args.prune_ablation:
+        return prune_ablation(args)
 
     import torch
     import paper_2506_08276_amd as L

@@ -227,7 +227,7 @@ int leann_search_updates(leann_ctx *ctx, const float *queries_dev, int64_t nq, c
  *   row_ptr_dev uint64[n + 1], col_idx_dev uint32 with room for n * M entries (device,
  *   caller-owned); n_edges_host receives the edge count.  Scratch is allocated and freed
  *   inside the call (n * (M + batch) * 4 + batch * n * 2 bytes).  Synchronises the stream.
- * Errors: efC outside 1..256, M outside 1..64, m outside 1..M, batch outside 1..256,
+ * Errors: efC outside 1..256, M outside 1..64, m outside 1..M, batch outside 1..1024,
  * ramp < 1, n >= 2^31 -> LEANN_EINVAL.
  */
 int leann_build_graph(leann_ctx *ctx, const float *emb_dev, int64_t n, int32_t d, const uint8_t *is_hub_dev,

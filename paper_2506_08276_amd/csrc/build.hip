@@ -13,7 +13,7 @@ namespace {
 
 constexpr int EFC_MAX = 256;    // construction queue length
 constexpr int M_MAX = 64;       // degree cap
-constexpr int BATCH_MAX = 256;  // nodes per batch
+constexpr int BATCH_MAX = 1024;  // nodes per batch
 constexpr int LIST_MAX = M_MAX + BATCH_MAX;
 
 struct BuildState {

@@ -34,7 +34,7 @@ def gpu_csr(rp, ci):
 
 
 @pytest.mark.parametrize("n,batch,ramp,hubs", [(300, 1, 1, False), (300, 1, 1, True), (301, 8, 2, True),
-                                                (700, 256, 8, False), (257, 32, 1, True)])
+                                                (700, 256, 8, False), (3000, 1024, 2, True), (257, 32, 1, True)])
 def test_construction_identical_on_exact_arithmetic(L, orc, ctx, n, batch, ramp, hubs):
     rng = np.random.default_rng(n + batch)
     d, efC, M, m = 8, 24, 8, 3
@@ -112,7 +112,7 @@ def test_real_valued_corpus_promises_and_quality(L, orc, ctx):
 def test_argument_checks(L, ctx):
     emb = to_dev(np.ones((10, 4), np.float32))
     for kw in (dict(efC=0, M=4), dict(efC=300, M=4), dict(efC=8, M=65), dict(efC=8, M=4, m=5),
-               dict(efC=8, M=4, batch=257), dict(efC=8, M=4, ramp=0)):
+               dict(efC=8, M=4, batch=1025), dict(efC=8, M=4, ramp=0)):
         with pytest.raises(L.LeannError) as ei:
             L.leann_build_graph(ctx, emb, **kw)
         assert ei.value.status == -1
