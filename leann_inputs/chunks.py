@@ -55,6 +55,8 @@ def topic_chunks(topics, n, seq, len_lo, len_hi, seed, topic_frac=0.7, block=327
         tk = np.where(pick, topics["subsets"][topic[s:e, None], rank_t], topics["background"][rank_b])
         tk[np.arange(seq)[None, :] >= lengths[s:e, None]] = 0
         tokens[s:e] = tk
+        if progress is not None:
+            progress(e, n)
     return tokens, lengths, topic
 
 
@@ -111,6 +113,8 @@ def variants_of(topics, corpus, family, seq, rng, resample, topic_frac, block=32
         tk = np.where(redo, fresh, base[family[s:e]])
         tk[np.arange(seq)[None, :] >= lengths[s:e, None]] = 0
         tokens[s:e] = tk
+        if progress is not None:
+            progress(e, n)
     return tokens, lengths
 
 
@@ -164,7 +168,7 @@ def _latent_draws(space, z, seq, rng, bg_frac, jitter):
 
 
 def latent_corpus(space, n, seq, len_lo, len_hi, seed, family_size=4, resample=0.3, bg_frac=0.25, jitter=0.7,
-                  len_jitter=4, block=16384):
+                  len_jitter=4, block=16384, progress=None):
     """Corpus of near-duplicate families placed uniformly on the latent torus.
 
     Each family has a position z and a base chunk drawn at z; every corpus chunk is a variant of its family's
@@ -181,12 +185,12 @@ def latent_corpus(space, n, seq, len_lo, len_hi, seed, family_size=4, resample=0
     family = (rng.permutation(n_fam * family_size)[:n] // family_size).astype(np.int32)
     corpus = dict(base=base, z=z, base_len=base_len, len_lo=len_lo, len_hi=len_hi, len_jitter=len_jitter,
                   resample=resample, bg_frac=bg_frac, jitter=jitter, seq=seq)
-    tokens, lengths = latent_variants(space, corpus, family, rng, block)
+    tokens, lengths = latent_variants(space, corpus, family, rng, block, progress)
     corpus.update(tokens=tokens, lengths=lengths, family=family)
     return corpus
 
 
-def latent_variants(space, corpus, family, rng, block=16384):
+def latent_variants(space, corpus, family, rng, block=16384, progress=None):
     n, seq = len(family), corpus["seq"]
     tokens = np.empty((n, seq), dtype=np.int32)
     j = corpus["len_jitter"]
@@ -199,6 +203,8 @@ def latent_variants(space, corpus, family, rng, block=16384):
         tk = np.where(redo, fresh, corpus["base"][family[s:e]])
         tk[np.arange(seq)[None, :] >= lengths[s:e, None]] = 0
         tokens[s:e] = tk
+        if progress is not None:
+            progress(e, n)
     return tokens, lengths
 
 
