@@ -203,7 +203,7 @@ void leann_destroy(leann_ctx *ctx)
     if (!ctx) return;
     (void)hipSetDevice(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
-    DevBuf *bufs[] = {&ctx->w_bf16, &ctx->w_f32, &ctx->x, &ctx->qkv, &ctx->att, &ctx->pre, &ctx->hid, &ctx->cu,
+    DevBuf *bufs[] = {&ctx->w_bf16, &ctx->w_f32, &ctx->x, &ctx->qkv, &ctx->att, &ctx->delta, &ctx->hid, &ctx->cu,
                       &ctx->len, &ctx->meta, &ctx->enc_ids, &ctx->s_state, &ctx->s_emb, &ctx->s_lut, &ctx->s_seen,
                       &ctx->s_misc, &ctx->s_owner, &ctx->s_buf};
     for (DevBuf *b : bufs) b->release();

@@ -60,7 +60,7 @@ struct leann_ctx {
     int64_t max_tokens = 1048576;  // padded tokens per encoder pass (workspaces: about 17 KB per token at BERT-base width)
     int32_t aq_capacity = 0;  // 0 = derive from ef and graph
     // encoder workspace
-    DevBuf x, qkv, att, pre, hid, cu, len, meta, enc_ids;
+    DevBuf x, qkv, att, delta, hid, cu, len, meta, enc_ids;
     // search workspace
     DevBuf s_state, s_emb, s_lut, s_seen, s_misc, s_owner, s_buf;
     // optional per-kernel timing (leann_profile_begin / leann_profile_end)

@@ -415,12 +415,12 @@ int enc_forward(leann_ctx *ctx, const leann_chunks *chunks, const int64_t *ids_d
     LEANN_TRY(ctx->x.reserve(rows * d * sizeof(bf16_t)));
     LEANN_TRY(ctx->qkv.reserve(rows * 3 * d * sizeof(bf16_t)));
     LEANN_TRY(ctx->att.reserve(rows * d * sizeof(bf16_t)));
-    LEANN_TRY(ctx->pre.reserve(rows * d * sizeof(bf16_t)));
+    LEANN_TRY(ctx->delta.reserve(rows * d * sizeof(bf16_t)));
     LEANN_TRY(ctx->hid.reserve(rows * F * sizeof(bf16_t)));
     LEANN_TRY(ctx->cu.reserve((size_t)(per_pass + 1) * sizeof(int32_t)));
     LEANN_TRY(ctx->enc_ids.reserve((size_t)per_pass * sizeof(int64_t)));
     bf16_t *x = (bf16_t *)ctx->x.p, *qkv = (bf16_t *)ctx->qkv.p, *att = (bf16_t *)ctx->att.p, *hid = (bf16_t *)ctx->hid.p;
-    bf16_t *delta = (bf16_t *)ctx->pre.p;  // sublayer output waiting for its residual add + LayerNorm
+    bf16_t *delta = (bf16_t *)ctx->delta.p;  // sublayer output waiting for its residual add + LayerNorm
     int32_t *cu = (int32_t *)ctx->cu.p;
     int64_t *chunk_of = (int64_t *)ctx->enc_ids.p;
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)(d / H));
