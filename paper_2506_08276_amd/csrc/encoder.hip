@@ -286,7 +286,7 @@ __global__ __launch_bounds__(256, NKT == 4 ? 3 : 2) void attention_kernel(const 
             if (t < nkt) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    float p = exp2f(sc[t][r] * scale_log2e - moff);
+                    float p = __builtin_amdgcn_exp2f(sc[t][r] * scale_log2e - moff);  // argument <= 0: no overflow, underflow to 0 is exact enough
                     sc[t][r] = p;
                     den += p;
                 }
