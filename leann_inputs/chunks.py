@@ -55,8 +55,6 @@ def topic_chunks(topics, n, seq, len_lo, len_hi, seed, topic_frac=0.7, block=327
         tk = np.where(pick, topics["subsets"][topic[s:e, None], rank_t], topics["background"][rank_b])
         tk[np.arange(seq)[None, :] >= lengths[s:e, None]] = 0
         tokens[s:e] = tk
-        if progress is not None:
-            progress(e, n)
     return tokens, lengths, topic
 
 
@@ -113,8 +111,6 @@ def variants_of(topics, corpus, family, seq, rng, resample, topic_frac, block=32
         tk = np.where(redo, fresh, base[family[s:e]])
         tk[np.arange(seq)[None, :] >= lengths[s:e, None]] = 0
         tokens[s:e] = tk
-        if progress is not None:
-            progress(e, n)
     return tokens, lengths
 
 
