@@ -307,6 +307,30 @@ def prune_ablation(args):
               flush=True)
 
 
+def parameter_sweep(args):
+    """--sweep: recall@3, queries/s and recomputed chunks per query over the re-rank ratio, the batch threshold and
+    the queue length (the N = 500k configuration: alpha in {0.05, 0.1, 0.2, 0.5} x B in {64, 128, 256} x ef in
+    {50, 100, 200}); one leann_search call per point, timed with the host clock around the call."""
+    import torch
+    import paper_2506_08276_amd as L
+    L.load_library()
+    world = build_world(args, L, torch)
+    for alpha in (0.05, 0.1, 0.2, 0.5):
+        for batch in (64, 128, 256):
+            for ef in (50, 100, 200):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                ids, _, st = L.leann_search(world["ctx"], world["queries"], world["graph"], world["pq"], world["t"],
+                                            world["l"], ef, args.k, alpha, batch)
+                torch.cuda.synchronize()
+                dt = time.perf_counter() - t0
+                print(json.dumps({"mode": "sweep", "n": args.n, "nq": args.nq, "rerank_ratio": alpha, "batch": batch, "ef": ef,
+                                  "recall_at_3": recall_at_3(ids, world["gt"]), "queries_per_s": args.nq / dt,
+                                  "recomputed_chunks_per_query": st["recomputed_chunks"] / args.nq,
+                                  "encoded_chunks_per_query": st["encoded_chunks"] / args.nq, "rounds": st["rounds"],
+                                  "flushes_per_query": st["flushes"] / args.nq}), flush=True)
+
+
 def cpu_baseline(world, recomputed_per_query, seconds_target=15.0):
     """The oracle as it stands, on a bounded sample of the same workload: oracle chunks/s over a few chunks per
     core, and queries/s derived as chunks/s / (recomputed chunks per query measured on the GPU run)."""
@@ -365,6 +389,7 @@ def main():
                     help="with --encoder-only: BERT-base shape (12 x 768) or the 34 M-parameter 12 x 384 encoder")
     ap.add_argument("--profile-pass", action="store_true", help="with --encoder-only: a single 2048-chunk batch")
     ap.add_argument("--adc-microbench", action="store_true", help="run only the stand-alone ADC scorer table")
+    ap.add_argument("--sweep", action="store_true", help="re-rank ratio x batch x ef grid on the search workload")
     ap.add_argument("--prune-ablation", action="store_true", help="graph construction variants: recall vs recomputation")
     ap.add_argument("--prune-M", type=int, default=64)
     ap.add_argument("--prune-m", type=int, default=16)
@@ -381,6 +406,8 @@ def main():
         return adc_microbench(args)
     if args.prune_ablation:
         return prune_ablation(args)
+    if args.sweep:
+        return parameter_sweep(args)
 
     import torch
     import paper_2506_08276_amd as L
