@@ -10,8 +10,10 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_SRC = os.path.join(_HERE, "leann_oracle.c")
-_LIB = os.path.join(_HERE, "libleann_oracle.so")
+# LEANN_ORACLE_SRC points the binding at another copy of the source (the test that plants mistakes in the oracle and
+# checks that the pins notice uses it); the library is then built next to that copy
+_SRC = os.environ.get("LEANN_ORACLE_SRC") or os.path.join(_HERE, "leann_oracle.c")
+_LIB = os.path.join(os.path.dirname(_SRC), "libleann_oracle.so")
 _lib = None
 
 __all__ = [

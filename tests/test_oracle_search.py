@@ -132,6 +132,30 @@ def test_ef_at_least_n_gives_exact_topk(orc, world):
             assert r["stats"]["recomputed"] == w["n"]  # every node scored exactly once
 
 
+def test_equal_scores_are_ordered_by_id(orc):
+    """The total order is (score descending, id ascending): with duplicated vectors (integer coordinates, so equal
+    vectors give bit-equal scores) every tie has to come out lower id first, in the result and in the queue rule."""
+    rng = np.random.default_rng(4)
+    base = rng.integers(-3, 4, size=(40, 8)).astype(np.float32)
+    table = base[rng.integers(0, 40, 160)]                      # every vector about four times
+    n, d = table.shape
+    nbr, _ = li.knn_graph(table, 6)
+    row_ptr, col_idx = li.to_csr(li.add_ring(list(nbr)))
+    cb, _ = orc.pq_train(table, 2, 3, 1, ksub=16)
+    codes = orc.pq_encode(table, cb)
+    for qi in range(5):
+        q = base[qi] + 0.0
+        r = orc.search_table(q, row_ptr, col_idx, 0, cb, codes, table, ef=n, k=12, alpha=1.0, batch=5)
+        s = table @ q
+        want = np.lexsort((np.arange(n), -s))[:12]              # written out: score descending, then id ascending
+        assert list(r["ids"]) == list(want)
+        assert len(set(s[want].tolist())) < 12                  # the case does contain ties
+        # a short queue: the tail of EQ is decided by the same rule
+        r2 = orc.search_table(q, row_ptr, col_idx, 0, cb, codes, table, ef=6, k=6, alpha=1.0, batch=1)
+        order = np.lexsort((r2["log_ids"], -r2["log_scores"].astype(np.float64)))[:6]
+        assert list(r2["ids"]) == list(r2["log_ids"][order])
+
+
 def test_exact_topk_is_brute_force(orc, world):
     w = world
     for q in w["queries"][:4]:
