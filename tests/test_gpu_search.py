@@ -157,6 +157,21 @@ def test_pending_updates_against_oracle(L, orc, world, ef, k, alpha, batch):
     assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
 
 
+def test_more_queries_than_one_group(L, world):
+    """A call with more queries than the library advances together (groups of 4096): every copy of a query gets the
+    answer of that query alone."""
+    import torch
+    w = world
+    reps = 4096 // w["q"].shape[0] + 40
+    many = w["q"].repeat(reps, 1).contiguous()
+    say(f"{many.shape[0]} queries in one call (stored embeddings)")
+    ids, sc, st = L.leann_search(w["ctx"], many, w["graph"], w["pq"], w["t"], w["l"], 32, 3, 0.2, 32, cache=w["full_cache"])
+    ids1, sc1, st1 = L.leann_search(w["ctx"], w["q"], w["graph"], w["pq"], w["t"], w["l"], 32, 3, 0.2, 32,
+                                    cache=w["full_cache"])
+    assert torch.equal(ids, ids1.repeat(reps, 1)) and torch.equal(sc, sc1.repeat(reps, 1))
+    assert st["hops"] == reps * st1["hops"] and st["recomputed_chunks"] == reps * st1["recomputed_chunks"]
+
+
 def decided_ranks(log_scores, k, gap=1e-3):
     """Ranks (0-based) of the oracle's top-k whose score is more than `gap` away from both neighbours in the
     oracle's sorted list of exact scores: there the id is decided by more than the precision difference."""
