@@ -208,18 +208,7 @@ class Updates(C.Structure):
                 ("buffer_n", C.c_int64)]
 
 
-def leann_search_updates(ctx, queries, graph, pq, tokens, lengths, ef, k, rerank_ratio, batch, cache=None,
-                         deleted_bits=None, buffer=None):
-    """leann_search with pending updates: deleted_bits = int32 CUDA tensor of (n + 31) // 32 words (bit v set: node v
-    is soft-deleted) or None; buffer = (ids int32 CUDA tensor holding uint32 [nb], emb float32 [nb][d]) or None."""
-    return leann_search(ctx, queries, graph, pq, tokens, lengths, ef, k, rerank_ratio, batch, cache=cache,
-                        _updates=(deleted_bits, buffer))
-
-
-def leann_search(ctx, queries, graph, pq, tokens, lengths, ef, k, rerank_ratio, batch, cache=None, _updates=None):
-    """graph = (row_ptr int64 CUDA tensor holding uint64 values, col_idx int32 CUDA tensor holding uint32, entry).
-    cache = (slot_of int32 [n], emb float32 [rows][d]) or None.
-    Returns (ids int64 [nq][k], scores float32 [nq][k], stats dict)."""
+def _search(entry_point, ctx, queries, graph, pq, tokens, lengths, ef, k, rerank_ratio, batch, cache, updates):
     _dev(queries, torch.float32, "queries")
     row_ptr, col_idx, entry = graph
     _dev(row_ptr, torch.int64, "row_ptr")
@@ -237,8 +226,12 @@ def leann_search(ctx, queries, graph, pq, tokens, lengths, ef, k, rerank_ratio, 
         _dev(emb, torch.float32, "cache emb")
         cstruct = EmbCache(slot_of.data_ptr(), emb.data_ptr(), emb.shape[0])
         cref = C.byref(cstruct)
-    if _updates is not None:
-        deleted_bits, buffer = _updates
+    head = (ctx, _ptr(queries), C.c_int64(nq), C.byref(g), pq, C.byref(ch), cref)
+    tail = (C.c_int32(ef), C.c_int32(k), C.c_float(rerank_ratio), C.c_int32(batch), _ptr(ids), _ptr(scores), C.byref(st))
+    if entry_point == "leann_search":
+        _check(load_library().leann_search(*head, *tail))
+    else:
+        deleted_bits, buffer = updates
         u = Updates(None, None, None, 0)
         if deleted_bits is not None:
             _dev(deleted_bits, torch.int32, "deleted_bits")
@@ -250,14 +243,23 @@ def leann_search(ctx, queries, graph, pq, tokens, lengths, ef, k, rerank_ratio, 
             _dev(buf_emb, torch.float32, "buffer emb")
             assert buf_emb.shape == (buf_ids.numel(), queries.shape[1])
             u.buffer_emb, u.buffer_ids, u.buffer_n = buf_emb.data_ptr(), buf_ids.data_ptr(), buf_ids.numel()
-        _check(load_library().leann_search_updates(ctx, _ptr(queries), C.c_int64(nq), C.byref(g), pq, C.byref(ch), cref,
-                                                   C.byref(u), C.c_int32(ef), C.c_int32(k), C.c_float(rerank_ratio),
-                                                   C.c_int32(batch), _ptr(ids), _ptr(scores), C.byref(st)))
-        return ids, scores, st.as_dict()
-    _check(load_library().leann_search(ctx, _ptr(queries), C.c_int64(nq), C.byref(g), pq, C.byref(ch), cref,
-                                       C.c_int32(ef), C.c_int32(k), C.c_float(rerank_ratio), C.c_int32(batch),
-                                       _ptr(ids), _ptr(scores), C.byref(st)))
+        _check(load_library().leann_search_updates(*head, C.byref(u), *tail))
     return ids, scores, st.as_dict()
+
+
+def leann_search(ctx, queries, graph, pq, tokens, lengths, ef, k, rerank_ratio, batch, cache=None):
+    """graph = (row_ptr int64 CUDA tensor holding uint64 values, col_idx int32 CUDA tensor holding uint32, entry).
+    cache = (slot_of int32 [n], emb float32 [rows][d]) or None.
+    Returns (ids int64 [nq][k], scores float32 [nq][k], stats dict)."""
+    return _search("leann_search", ctx, queries, graph, pq, tokens, lengths, ef, k, rerank_ratio, batch, cache, None)
+
+
+def leann_search_updates(ctx, queries, graph, pq, tokens, lengths, ef, k, rerank_ratio, batch, cache=None,
+                         deleted_bits=None, buffer=None):
+    """leann_search with pending updates: deleted_bits = int32 CUDA tensor of (n + 31) // 32 words (bit v set: node v
+    is soft-deleted) or None; buffer = (ids int32 CUDA tensor holding uint32 [nb], emb float32 [nb][d]) or None."""
+    return _search("leann_search_updates", ctx, queries, graph, pq, tokens, lengths, ef, k, rerank_ratio, batch, cache,
+                   (deleted_bits, buffer))
 
 
 def leann_build_graph(ctx, emb, efC, M, m=None, is_hub=None, batch=256, ramp=8):
