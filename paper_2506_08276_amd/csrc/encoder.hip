@@ -374,8 +374,8 @@ int launch_gemm(leann_ctx *ctx, int prof_kind, const bf16_t *A, const bf16_t *W,
 {
     static bool attr_done = false;
     constexpr int WM = 2, WN = (BM * BN <= 128 * 128) ? 2 : 4;
-    constexpr int smem = 3 * (BM + BN) * GEMM_BK * (int)sizeof(bf16_t);
-    if (N % BN || K % (4 * GEMM_BK)) {
+    constexpr int smem = gemm_smem_bytes<BM, BN, WM, WN>();
+    if (N % BN || K % (4 * GEMM_BK) || (BM * BN > 128 * 128 && K < 8 * GEMM_BK)) {
         leann_set_error("GEMM shape N=%d K=%d not covered by the %dx%d tile", N, K, BM, BN);
         return LEANN_ESHAPE;
     }

@@ -17,6 +17,10 @@ namespace {
 // The 256x256 tile (eight waves of 128x64) halves the bytes fetched from L2 per flop compared with 128x128,
 // which is what bounds the small tile.  Each output element is one fixed-order sum over K: a row's result does
 // not depend on T.
+// Vector-memory loads return in order, so a wait for any load is a wait for every load issued before it.  The
+// kernel is written so that no wait falls behind the prefetched slabs: no register spills (a reload is a load),
+// no load whose result is unused, the bias fetched ahead of the slabs and kept in LDS, per-lane values of the
+// epilogue recomputed per tile instead of held in registers.
 enum { EPI_BIAS = 0, EPI_BIAS_GELU = 1 };
 
 // GELU(v) = v Phi(v) with the normal distribution function written as a logistic function of an odd polynomial,
@@ -32,6 +36,13 @@ __device__ inline float gelu_erf(float v)
 
 constexpr int GEMM_BK = 32;
 
+// dynamic LDS of a block: three operand stages and, per wave, the bias of its 64 output columns
+template <int BM, int BN, int WM, int WN>
+constexpr int gemm_smem_bytes()
+{
+    return 3 * (BM + BN) * GEMM_BK * (int)sizeof(bf16_t) + WM * WN * 64 * (int)sizeof(float);
+}
+
 template <int BM, int BN, int WM, int WN, int EPI>
 __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4) ? 2 : 1) void gemm_kernel(
     const bf16_t *__restrict__ A, const bf16_t *__restrict__ W, const float *__restrict__ bias,
@@ -41,7 +52,9 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4) ? 2 : 1) void gemm_ker
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     bf16_t *As = reinterpret_cast<bf16_t *>(smem);  // [3][BM][BK]
     bf16_t *Bs = As + 3 * BM * BK;                  // [3][BN][BK]
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // the same for the whole wave: a scalar register
+    float *wbias = reinterpret_cast<float *>(Bs + 3 * BN * BK) + wave * 64;  // this wave's 64 bias values
     const int wm = wave / WN, wn = wave % WN;
     constexpr int NT = 64 * WM * WN;                     // threads per block
     constexpr int TM = BM / WM / 32, TN = BN / WN / 32;  // 32x32 MFMA tiles per wave
@@ -61,11 +74,17 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4) ? 2 : 1) void gemm_ker
     const int lrow = tid >> 2, lc = tid & 3;
     const int soff = lrow * BK + ((lc ^ ((lrow >> 2) & 3)) << 3);  // rows RPP apart share the swizzle term
 
+    // Operand loads are buffer loads: a descriptor per tile (scalar registers: base of the tile's BM or BN rows, size
+    // of those rows, so a load can never leave the tile), one 32-bit byte offset per thread that A and W share, and a
+    // scalar offset for the chunk and the K-slab.  No 64-bit vector address arithmetic and no per-thread pointers.
+    const int toff = (lrow * K + lc * 8) * (int)sizeof(bf16_t);
+#define GEMM_RSRC(ptr, rows)                                                                             \
+    __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(ptr), 0, (rows) * K * (int)sizeof(bf16_t), 0x00020000)
 #define GEMM_GLOAD(RA, RB, AP, WP, k0)                                                                   \
     _Pragma("unroll") for (int i = 0; i < ACH; ++i)                                                      \
-        RA[i] = *reinterpret_cast<const u32x4 *>((AP) + (size_t)(RPP * i) * K + (k0));                    \
+        RA[i] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(AP, toff, ((RPP * i) * K + (k0)) * 2, 0)); \
     _Pragma("unroll") for (int i = 0; i < BCH; ++i)                                                      \
-        RB[i] = *reinterpret_cast<const u32x4 *>((WP) + (size_t)(RPP * i) * K + (k0));
+        RB[i] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(WP, toff, ((RPP * i) * K + (k0)) * 2, 0));
 #define GEMM_SSTORE(RA, RB, stage)                                                                       \
     _Pragma("unroll") for (int i = 0; i < ACH; ++i)                                                      \
         *reinterpret_cast<u32x4 *>(As + (stage) * BM * BK + RPP * BK * i + soff) = RA[i];                 \
@@ -73,30 +92,20 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4) ? 2 : 1) void gemm_ker
         *reinterpret_cast<u32x4 *>(Bs + (stage) * BN * BK + RPP * BK * i + soff) = RB[i];
 
 
-    // operand fragments: lane l reads row (l & 31) of its 32-row block, 16-byte chunk 2*ks + (l >> 5)
-    int a_off[TM][2], b_off[TN][2];
+    // operand fragments: lane l reads row (l & 31) of a 32-row block, 16-byte chunk 2*ks + (l >> 5).  The block's
+    // first row is a multiple of 32, so the swizzle term depends on the lane only: two offsets serve every block.
+    int foff[2];
 #pragma unroll
-    for (int mi = 0; mi < TM; ++mi) {
-        const int row = wm * (BM / WM) + mi * 32 + (lane & 31);
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) a_off[mi][ks] = row * BK + (((ks * 2 + (lane >> 5)) ^ ((row >> 2) & 3)) << 3);
-    }
-#pragma unroll
-    for (int ni = 0; ni < TN; ++ni) {
-        const int row = wn * (BN / WN) + ni * 32 + (lane & 31);
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) b_off[ni][ks] = row * BK + (((ks * 2 + (lane >> 5)) ^ ((row >> 2) & 3)) << 3);
-    }
-
+    for (int ks = 0; ks < 2; ++ks) foff[ks] = (lane & 31) * BK + (((ks * 2 + (lane >> 5)) ^ ((lane >> 2) & 3)) << 3);
 #define GEMM_FRAGS(AF, BF, stage, ks)                                                                    \
     _Pragma("unroll") for (int mi = 0; mi < TM; ++mi)                                                    \
-        AF[mi] = *reinterpret_cast<const bf16x8 *>(As + (stage) * BM * BK + a_off[mi][ks]);               \
+        AF[mi] = *reinterpret_cast<const bf16x8 *>(As + (stage) * BM * BK + (wm * (BM / WM) + mi * 32) * BK + foff[ks]); \
     _Pragma("unroll") for (int ni = 0; ni < TN; ++ni)                                                    \
-        BF[ni] = *reinterpret_cast<const bf16x8 *>(Bs + (stage) * BN * BK + b_off[ni][ks]);
+        BF[ni] = *reinterpret_cast<const bf16x8 *>(Bs + (stage) * BN * BK + (wn * (BN / WN) + ni * 32) * BK + foff[ks]);
 #define GEMM_MFMA(AF, BF)                                                                                \
     _Pragma("unroll") for (int mi = 0; mi < TM; ++mi)                                                    \
         _Pragma("unroll") for (int ni = 0; ni < TN; ++ni)                                                \
-            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(AF[mi], BF[ni], acc[mi][ni], 0, 0, 0);
+            acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(BF[ni], AF[mi], acc[mi][ni], 0, 0, 0);
     // One iteration: LOAD prefetches slab kt+5 (or a slab of the next tile), the MFMAs multiply slab kt (its first
     // fragments are already in af0/bf0), STORE puts slab kt+2 into the ring while the MFMAs run, and the first
     // fragments of slab kt+1 are read.
@@ -150,9 +159,15 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4) ? 2 : 1) void gemm_ker
     GEMM_TILE_AT(0, have, tile_m, tile_n)
     if (!have) return;
     const int KT = K / BK;  // a multiple of 4: the host checks K % (4 * BK) == 0
-    const int klast = (KT - 1) * BK;
-    const bf16_t *ag = A + ((size_t)tile_m * BM + lrow) * K + lc * 8;
-    const bf16_t *wg = W + ((size_t)tile_n * BN + lrow) * K + lc * 8;
+    // The large tile is launched for K >= 8 slabs only (the host checks): without the short-K paths the compiler
+    // does not have to merge their pending loads into the waits of the long-K path.
+    if constexpr (BM * BN > 128 * 128) __builtin_assume(KT >= 8);
+    auto ag = GEMM_RSRC(A + (size_t)tile_m * BM * K, BM);
+    auto wg = GEMM_RSRC(W + (size_t)tile_n * BN * K, BN);
+    // The bias of a tile is fetched before the tile's first operand slab and put into LDS at the start of the tile:
+    // a load issued in the epilogue would complete only after the next tile's prefetched slabs (loads return in
+    // order), and the epilogue would wait for all of them.
+    float bnext = bias[tile_n * BN + wn * (BN / WN) + lane];
     GEMM_GLOAD(ra0, rb0, ag, wg, 0)
     GEMM_GLOAD(ra1, rb1, ag, wg, BK)
     GEMM_GLOAD(ra2, rb2, ag, wg, 2 * BK)
@@ -162,8 +177,8 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4) ? 2 : 1) void gemm_ker
     bool have_next;
     int next_m = tile_m, next_n = tile_n;
     GEMM_TILE_AT(step + 1, have_next, next_m, next_n)
-    const bf16_t *ag_next = A + ((size_t)next_m * BM + lrow) * K + lc * 8;
-    const bf16_t *wg_next = W + ((size_t)next_n * BN + lrow) * K + lc * 8;
+    const auto ag_next = GEMM_RSRC(A + (size_t)next_m * BM * K, BM);
+    const auto wg_next = GEMM_RSRC(W + (size_t)next_n * BN * K, BN);
     f32x16 acc[TM][TN];
 #pragma unroll
     for (int mi = 0; mi < TM; ++mi)
@@ -175,61 +190,82 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4) ? 2 : 1) void gemm_ker
     // Slabs 0..3 of this tile are in the four register sets.  Steady state of the K loop at iteration 0: slabs 0 and
     // 1 in the ring, slabs 2, 3, 4 in sets 1, 2, 3, set 0 free.
     bf16x8 af0[TM], bf0[TN], af1[TM], bf1[TN];
+    wbias[lane] = bnext;
     GEMM_SSTORE(ra0, rb0, 0)
     GEMM_SSTORE(ra1, rb1, 1)
 #pragma unroll
     for (int i = 0; i < ACH; ++i) { ra1[i] = ra2[i]; ra2[i] = ra3[i]; }
 #pragma unroll
     for (int i = 0; i < BCH; ++i) { rb1[i] = rb2[i]; rb2[i] = rb3[i]; }
-    GEMM_GLOAD(ra3, rb3, ag, wg, min(4 * BK, klast))
+    if (KT > 4) { GEMM_GLOAD(ra3, rb3, ag, wg, 4 * BK) }
     __syncthreads();
     GEMM_FRAGS(af0, bf0, 0, 0)
     int st_cur = 0, st_nxt = 1, st_nn = 2;
-    // Loads beyond the last slab re-read the last one (no branch in the loop body keeps the staging arrays in
-    // registers); their LDS stores land in stages nobody reads any more.
-    for (int kt = 0; kt < KT - 4; kt += 4) {
-        GEMM_ITER(GEMM_GLOAD(ra0, rb0, ag, wg, min((kt + 5) * BK, klast)), GEMM_SSTORE(ra1, rb1, st_nn))
-        GEMM_ITER(GEMM_GLOAD(ra1, rb1, ag, wg, min((kt + 6) * BK, klast)), GEMM_SSTORE(ra2, rb2, st_nn))
-        GEMM_ITER(GEMM_GLOAD(ra2, rb2, ag, wg, min((kt + 7) * BK, klast)), GEMM_SSTORE(ra3, rb3, st_nn))
-        GEMM_ITER(GEMM_GLOAD(ra3, rb3, ag, wg, min((kt + 8) * BK, klast)), GEMM_SSTORE(ra0, rb0, st_nn))
+    // Every load is of a slab that exists: the last group of four before the tail has one load fewer.  (A load
+    // whose result nobody uses costs more than its bytes: its registers are reused at once, and that has to wait for
+    // it and, as loads return in order, for every load issued before it.)
+    for (int kt = 0; kt < KT - 8; kt += 4) {
+        GEMM_ITER(GEMM_GLOAD(ra0, rb0, ag, wg, (kt + 5) * BK), GEMM_SSTORE(ra1, rb1, st_nn))
+        GEMM_ITER(GEMM_GLOAD(ra1, rb1, ag, wg, (kt + 6) * BK), GEMM_SSTORE(ra2, rb2, st_nn))
+        GEMM_ITER(GEMM_GLOAD(ra2, rb2, ag, wg, (kt + 7) * BK), GEMM_SSTORE(ra3, rb3, st_nn))
+        GEMM_ITER(GEMM_GLOAD(ra3, rb3, ag, wg, (kt + 8) * BK), GEMM_SSTORE(ra0, rb0, st_nn))
+    }
+    if (KT >= 8) {
+        GEMM_ITER(GEMM_GLOAD(ra0, rb0, ag, wg, (KT - 3) * BK), GEMM_SSTORE(ra1, rb1, st_nn))
+        GEMM_ITER(GEMM_GLOAD(ra1, rb1, ag, wg, (KT - 2) * BK), GEMM_SSTORE(ra2, rb2, st_nn))
+        GEMM_ITER(GEMM_GLOAD(ra2, rb2, ag, wg, (KT - 1) * BK), GEMM_SSTORE(ra3, rb3, st_nn))
+        GEMM_ITER(, GEMM_SSTORE(ra0, rb0, st_nn))
     }
     // last four slabs: slabs KT-2 and KT-1 still go into the ring; the loads fetch the next tile
+    bnext = bias[next_n * BN + wn * (BN / WN) + lane];
     GEMM_ITER(GEMM_GLOAD(ra0, rb0, ag_next, wg_next, 0), GEMM_SSTORE(ra1, rb1, st_nn))
     GEMM_ITER(GEMM_GLOAD(ra1, rb1, ag_next, wg_next, BK), GEMM_SSTORE(ra2, rb2, st_nn))
     GEMM_ITER(GEMM_GLOAD(ra2, rb2, ag_next, wg_next, 2 * BK), )
     GEMM_ITER(GEMM_GLOAD(ra3, rb3, ag_next, wg_next, 3 * BK), )
 
-    // Epilogue.  Accumulator register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32 of its 32x32
-    // tile: a lane owns single elements of many rows.  Each wave transposes 32 rows at a time through its own
-    // slice of LDS so that the global stores are 16 bytes per lane and whole 128-byte row segments per 8 lanes.
+    // Epilogue.  The MFMAs take the W fragment as their first operand, so a 32x32 accumulator holds the transposed
+    // output block: lane l owns output row l%32 and, in registers 4g..4g+3, the four adjacent columns
+    // 8g + 4*(l/32) + 0..3.  Each wave passes 32 rows at a time through its own 4 KB of LDS: 8-byte stores of four
+    // bf16 (unit u of a row sits at position u ^ swz(row): the 16 lanes served together hit all banks once), then
+    // 16-byte reads, so that the global stores are whole 128-byte row segments per 8 lanes.
     __syncthreads();  // every wave is done with the operand stages
     constexpr int WCOLS = BN / WN;
-    constexpr int EROW = WCOLS * 2 + 16;  // staged row pitch in bytes (the pad spreads the banks)
-    unsigned char *stg = smem + wave * 32 * EROW;
+    static_assert(WCOLS == 64, "the epilogue's staging layout is written for 64 output columns per wave");
+    unsigned char *stg = smem + wave * 32 * 128;
     const int col0 = tile_n * BN + wn * WCOLS;
     const int row0 = tile_m * BM + wm * (BM / WM);
-    float bv[TN];
-#pragma unroll
-    for (int ni = 0; ni < TN; ++ni) bv[ni] = bias[col0 + ni * 32 + (lane & 31)];
-    // write-out geometry: a wave-wide access covers RPI rows of CPRW 16-byte chunks.  The output is read by a later
-    // kernel only: streaming stores keep it from displacing the operand slabs in L2 (measured: 3-7% per GEMM).
-    constexpr int CPRW = WCOLS / 8, RPI = 64 / CPRW, NJ = 32 / RPI;
-    const int orow = lane / CPRW, och = lane % CPRW;
+    // What the epilogue derives from the lane is computed here, per tile, instead of occupying registers through the
+    // K loop (the empty statement keeps the compiler from hoisting it).
+    int lane_e = lane;
+    asm volatile("" : "+v"(lane_e));
+    const int half = lane_e >> 5, l32 = lane_e & 31;
+    const int wswz = ((l32 & 7) << 1) | ((l32 >> 3) & 1);
+    const float *bp = wbias + 4 * half;
+    // write-out: a wave-wide access covers 8 rows of eight 16-byte chunks.  The output is read by a later kernel
+    // only: streaming stores keep it from displacing the operand slabs in L2 (measured: 3-7% per GEMM).
+    const int orow = lane_e >> 3, och = lane_e & 7;
 #pragma unroll
     for (int mi = 0; mi < TM; ++mi) {
 #pragma unroll
         for (int ni = 0; ni < TN; ++ni)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int lr = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3), lcol = ni * 32 + (lane & 31);
-                const float v = acc[mi][ni][r] + bv[ni];
-                *reinterpret_cast<bf16_t *>(stg + lr * EROW + lcol * 2) = (bf16_t)(EPI == EPI_BIAS_GELU ? gelu_erf(v) : v);
+            for (int g = 0; g < 4; ++g) {
+                const f32x4 bv = *reinterpret_cast<const f32x4 *>(bp + ni * 32 + 8 * g);  // one address per half-wave: a broadcast
+                bf16x4 o4;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float v = acc[mi][ni][4 * g + i] + bv[i];
+                    o4[i] = (bf16_t)(EPI == EPI_BIAS_GELU ? gelu_erf(v) : v);
+                }
+                const int u = ni * 8 + 2 * g + half;
+                *reinterpret_cast<bf16x4 *>(stg + l32 * 128 + ((u ^ wswz) << 3)) = o4;
             }
         __builtin_amdgcn_wave_barrier();  // LDS serves a wave's accesses in order: the reads below see the writes
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) {
-            const int lr = j * RPI + orow;
-            const u32x4 v = *reinterpret_cast<const u32x4 *>(stg + lr * EROW + och * 16);
+        for (int j = 0; j < 4; ++j) {
+            const int lr = j * 8 + orow;
+            u32x4 v = *reinterpret_cast<const u32x4 *>(stg + lr * 128 + ((och ^ orow) << 4));
+            if (j & 1) v = u32x4{v[2], v[3], v[0], v[1]};  // rows 8..15 and 24..31 hold the halves of a chunk swapped
             __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(out + (size_t)(row0 + mi * 32 + lr) * N + col0 + och * 8));
         }
         __builtin_amdgcn_wave_barrier();
@@ -243,6 +279,7 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4) ? 2 : 1) void gemm_ker
   }
 #undef GEMM_TILE_AT
 #undef GEMM_GLOAD
+#undef GEMM_RSRC
 #undef GEMM_SSTORE
 #undef GEMM_FRAGS
 #undef GEMM_MFMA
