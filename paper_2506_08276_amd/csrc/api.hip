@@ -131,6 +131,9 @@ int leann_create(leann_ctx **out, const leann_encoder_desc *desc, const void *we
         return LEANN_EINVAL;
     }
     LEANN_HIP(hipSetDevice(device));
+    LEANN_TRY(enc_init_device());
+    LEANN_TRY(pq_init_device());
+    LEANN_TRY(search_init_device());
     leann_ctx *ctx = new leann_ctx();
     ctx->desc = e;
     ctx->device = device;

@@ -91,6 +91,11 @@ struct leann_pq {
     int device = 0;
 };
 
+// Per-device set-up of each source file's kernels (LDS limits); called by leann_create with the device current.
+int enc_init_device();
+int pq_init_device();
+int search_init_device();
+
 // ---- encoder.hip
 // Embeds the chunks named by ids_dev[0..n) (NULL: first_id .. first_id+n) into out[n][d] (fp32), in passes of at
 // most ctx->max_tokens padded tokens.  err_dev: device int, set non-zero on invalid tokens / lengths / ids.

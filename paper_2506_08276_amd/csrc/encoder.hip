@@ -372,17 +372,11 @@ template <int BM, int BN, int EPI>
 int launch_gemm(leann_ctx *ctx, int prof_kind, const bf16_t *A, const bf16_t *W, const float *bias, bf16_t *out,
                 const int32_t *T_dev, int max_rows, int N, int K)
 {
-    static bool attr_done = false;
     constexpr int WM = 2, WN = (BM * BN <= 128 * 128) ? 2 : 4;
     constexpr int smem = gemm_smem_bytes<BM, BN, WM, WN>();
     if (N % BN || K % (4 * GEMM_BK) || (BM * BN > 128 * 128 && K < 8 * GEMM_BK)) {
         leann_set_error("GEMM shape N=%d K=%d not covered by the %dx%d tile", N, K, BM, BN);
         return LEANN_ESHAPE;
-    }
-    if (!attr_done) {
-        LEANN_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_kernel<BM, BN, WM, WN, EPI>),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, smem));
-        attr_done = true;
     }
     const int tiles_n = N / BN;
     const int tiles = ((max_rows + BM - 1) / BM) * tiles_n;
@@ -396,7 +390,28 @@ int launch_gemm(leann_ctx *ctx, int prof_kind, const bf16_t *A, const bf16_t *W,
     return LEANN_OK;
 }
 
+template <int BM, int BN, int EPI>
+int gemm_allow_lds()
+{
+    constexpr int WM = 2, WN = (BM * BN <= 128 * 128) ? 2 : 4;
+    LEANN_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_kernel<BM, BN, WM, WN, EPI>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, gemm_smem_bytes<BM, BN, WM, WN>()));
+    return LEANN_OK;
+}
+
 }  // namespace
+
+// Kernels that use more dynamic LDS than the default limit are allowed their size on the current device.
+int enc_init_device()
+{
+    LEANN_TRY((gemm_allow_lds<256, 256, EPI_BIAS>()));
+    LEANN_TRY((gemm_allow_lds<256, 256, EPI_BIAS_GELU>()));
+    LEANN_TRY((gemm_allow_lds<128, 128, EPI_BIAS>()));
+    LEANN_TRY((gemm_allow_lds<128, 128, EPI_BIAS_GELU>()));
+    LEANN_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(attention_kernel<8>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, AttCfg<8>::SMEM));
+    return LEANN_OK;
+}
 
 int enc_forward(leann_ctx *ctx, const leann_chunks *chunks, const int64_t *ids_dev, int64_t first_id, int64_t n,
                 float *out_dev, int *err_dev, int64_t *tok_count_dev)
@@ -431,12 +446,6 @@ int enc_forward(leann_ctx *ctx, const leann_chunks *chunks, const int64_t *ids_d
         return v ? atoi(v) : 256;
     }();
     const bool wide = tile_pref == 256 && d % 256 == 0 && F % 256 == 0;
-    static bool att_attr = false;
-    if (!att_attr) {
-        LEANN_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(attention_kernel<8>),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, AttCfg<8>::SMEM));
-        att_attr = true;
-    }
 
     for (int64_t s = 0; s < n; s += per_pass) {
         const int m = (int)((n - s < per_pass) ? n - s : per_pass);

@@ -229,6 +229,13 @@ int alloc_pq(leann_ctx *ctx, int64_t n, int32_t d, int32_t m_sub, bool own_codes
 
 }  // namespace
 
+int pq_init_device()
+{
+    LEANN_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(adc_kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
+    return LEANN_OK;
+}
+
 int pq_build_lut(leann_ctx *ctx, const float *queries_dev, int64_t nq, const leann_pq *pq, float *lut_dev)
 {
     if (nq <= 0) return LEANN_OK;
@@ -411,12 +418,6 @@ int leann_adc(leann_ctx *ctx, const float *queries_dev, int64_t nq, const leann_
     LEANN_HIP(hipMemsetAsync(err, 0, sizeof(int), ctx->stream));
     LEANN_TRY(pq_build_lut(ctx, queries_dev, nq, pq, (float *)ctx->s_lut.p));
     const int smem = pq->m_sub * KSUB * (int)sizeof(float);
-    static bool attr = false;
-    if (!attr) {
-        LEANN_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(adc_kernel),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
-        attr = true;
-    }
     if (smem > 96 * 1024) {
         leann_set_error("lookup table of %d bytes does not fit the ADC kernel's LDS budget", smem);
         return LEANN_ESHAPE;

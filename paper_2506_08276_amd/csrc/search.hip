@@ -462,6 +462,13 @@ size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 }  // namespace
 
+int search_init_device()
+{
+    LEANN_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(traverse_kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024));
+    return LEANN_OK;
+}
+
 int search_run(leann_ctx *ctx, const float *queries_dev, int64_t nq, const leann_graph *graph, const leann_pq *pq,
                const leann_chunks *chunks, const leann_emb_cache *cache, const leann_updates *upd, int32_t ef, int32_t k,
                float alpha, int32_t batch, int64_t *out_ids_dev, float *out_scores_dev, leann_search_stats *stats)
@@ -541,12 +548,6 @@ int search_run(leann_ctx *ctx, const float *queries_dev, int64_t nq, const leann
     if (trav_smem > 150 * 1024) {
         leann_set_error("lookup table + queue of %d bytes exceed the LDS budget", trav_smem);
         return LEANN_ESHAPE;
-    }
-    static bool attr = false;
-    if (!attr) {
-        LEANN_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(traverse_kernel),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize, 150 * 1024));
-        attr = true;
     }
 
     std::vector<hipEvent_t> evs;
