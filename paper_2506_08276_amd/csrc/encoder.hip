@@ -188,7 +188,8 @@ template <int NKT>
 struct AttCfg {
     static constexpr int LP = NKT * 32;           // padded key capacity
     static constexpr int VS = LP + 4;             // V^T row pitch (bf16): conflict-free 8-byte fragment reads
-    static constexpr int SMEM = (LP * 64 + 64 * VS) * (int)sizeof(bf16_t);
+    static constexpr int KV_BYTES = (LP * 64 + 64 * VS) * (int)sizeof(bf16_t);
+    static constexpr int SMEM = KV_BYTES + 4 * 16 * 128;  // plus, per wave, 16 output rows of 64 bf16
 };
 
 template <int NKT>
@@ -317,18 +318,38 @@ __global__ __launch_bounds__(256, NKT == 4 ? 3 : 2) void attention_kernel(const 
                     }
                 }
             }
-        if (qrow < L) {
-            const float inv = 1.0f / den;
-            bf16_t *op = out + (size_t)(t0 + qrow) * d + h * 64;
+        // The lane owns query l32 and, per (dt, g), the four adjacent outputs dt*32 + 8g + 4*half + 0..3.  Sixteen
+        // queries at a time go through the wave's own 2 KB of LDS (8-byte unit u of a row at position u ^ swz(row):
+        // the 16 lanes served together hit all banks once), so that the global stores are 16 bytes per lane and
+        // whole 128-byte lines per 8 lanes (stores of 8 bytes per lane to 32 rows cost a quarter of the kernel's time).
+        const float inv = 1.0f / den;
+        unsigned char *ostg = smem + AttCfg<NKT>::KV_BYTES + wave * (16 * 128);
+        const int r16 = l32 & 15;
+        const int wswz = ((r16 & 7) << 1) | (r16 >> 3);
+        const int orow = lane >> 3, och = lane & 7;
 #pragma unroll
-            for (int dt = 0; dt < 2; ++dt)
+        for (int hp = 0; hp < 2; ++hp) {
+            if ((l32 >> 4) == hp) {
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    bf16x4 o4;
+                for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) o4[i] = (bf16_t)(oacc[dt][4 * g + i] * inv);
-                    *reinterpret_cast<bf16x4 *>(op + dt * 32 + 8 * g + 4 * half) = o4;
-                }
+                    for (int g = 0; g < 4; ++g) {
+                        bf16x4 o4;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) o4[i] = (bf16_t)(oacc[dt][4 * g + i] * inv);
+                        const int u = dt * 8 + 2 * g + half;
+                        *reinterpret_cast<bf16x4 *>(ostg + r16 * 128 + ((u ^ wswz) << 3)) = o4;
+                    }
+            }
+            __builtin_amdgcn_wave_barrier();  // LDS serves a wave's accesses in order
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const int lr = j * 8 + orow, q = qb * 32 + hp * 16 + lr;
+                u32x4 v = *reinterpret_cast<const u32x4 *>(ostg + lr * 128 + ((och ^ orow) << 4));
+                if (j & 1) v = u32x4{v[2], v[3], v[0], v[1]};  // rows 8..15 hold the halves of a chunk swapped
+                if (q < L) __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(out + (size_t)(t0 + q) * d + h * 64 + och * 8));
+            }
+            __builtin_amdgcn_wave_barrier();
         }
     }
 }
