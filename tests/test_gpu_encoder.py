@@ -145,3 +145,32 @@ def test_small_shape_sample_matches_oracle(L, orc):
     assert np.abs(got[ids] - want_bf).max() <= TOL_BF16_MODE
     print("small sample max-abs vs fp32 oracle %.3e, vs bf16-mode oracle %.3e" %
           (np.abs(got[ids] - want).max(), np.abs(got[ids] - want_bf).max()))
+
+
+def test_width_256_takes_the_large_tile_at_its_shortest_k(L, orc):
+    """hidden = 256: the 256 x 256 GEMM tile with K = 256 (eight K-slabs, the fewest it is launched for: no
+    full group of four before the tail) and K = 1024; ragged rows; against the oracle.  The same chunks embedded in
+    a pass small enough for the 128 x 128 tile give the same bits (both tiles add the K-slabs in one order)."""
+    import torch
+    cfg = dict(layers=3, hidden=256, heads=4, ffn=1024, vocab=2000, max_pos=128, ln_eps=1e-12)
+    say("width-256 encoder, large and small GEMM tile")
+    w = li.encoder_weights(cfg, li.config_seed(2) + 21, bf16_exact=True)
+    tokens, lengths = li.uniform_chunks(100, 128, 1, cfg["vocab"], 16, 128, li.config_seed(2) + 22)
+    lengths[:4] = [1, 31, 77, 128]
+    ctx = L.leann_create(cfg, to_dev(w).to(torch.bfloat16))
+    try:
+        t, l = to_dev(tokens), to_dev(lengths)
+        got = L.leann_embed(ctx, t, l, hidden=256).cpu().numpy()            # 12800 padded rows: large tile
+        few = L.leann_embed(ctx, t, l, n_ids=32, hidden=256).cpu().numpy()  # 4096 padded rows: small tile
+    finally:
+        L.leann_destroy(ctx)
+    assert np.array_equal(got[:32], few)
+    ids = np.array([0, 1, 2, 3, 50, 99], np.int64)
+    e = orc.desc(**cfg)
+    want = orc.embed(e, w, tokens, lengths, ids=ids)
+    want_bf = orc.embed(e, w, tokens, lengths, ids=ids, precision=1)
+    assert np.isfinite(got).all()
+    assert np.abs(got[ids] - want).max() <= TOL_FP32
+    assert np.abs(got[ids] - want_bf).max() <= TOL_BF16_MODE
+    print("width-256 sample max-abs vs fp32 oracle %.3e, vs bf16-mode oracle %.3e" %
+          (np.abs(got[ids] - want).max(), np.abs(got[ids] - want_bf).max()))
