@@ -215,8 +215,15 @@ def single_query_leg(L, torch, world, args, ef, count=20):
         rec += st["recomputed_chunks"]
         rounds += st["rounds"]
     n = len(times)
+    # the same queries once more with an event pair around every kernel: how much of the latency is kernel time
+    L.leann_profile_begin(world["ctx"])
+    for i in range(n):
+        one(i)
+    prof = L.leann_profile_end(world["ctx"])
     return {"queries": n, "mean_ms": 1e3 * sum(times) / n, "max_ms": 1e3 * max(times),
-            "recomputed_chunks_per_query": rec / n, "rounds_per_query": rounds / n}
+            "recomputed_chunks_per_query": rec / n, "rounds_per_query": rounds / n,
+            "kernel_ms_per_query": sum(prof["ms"].values()) / n,
+            "kernel_launches_per_query": sum(prof["launches"].values()) / n}
 
 
 def hub_cache_leg(L, torch, world, args, ef, qps_plain, ids_plain):

@@ -393,7 +393,7 @@ template <int BM, int BN, int EPI>
 int launch_gemm(leann_ctx *ctx, int prof_kind, const bf16_t *A, const bf16_t *W, const float *bias, bf16_t *out,
                 const int32_t *T_dev, int max_rows, int N, int K)
 {
-    constexpr int WM = 2, WN = (BM * BN <= 128 * 128) ? 2 : 4;
+    constexpr int WM = 2, WN = BN / 64;
     constexpr int smem = gemm_smem_bytes<BM, BN, WM, WN>();
     if (N % BN || K % (4 * GEMM_BK) || (BM * BN > 128 * 128 && K < 8 * GEMM_BK)) {
         leann_set_error("GEMM shape N=%d K=%d not covered by the %dx%d tile", N, K, BM, BN);
@@ -402,7 +402,7 @@ int launch_gemm(leann_ctx *ctx, int prof_kind, const bf16_t *A, const bf16_t *W,
     const int tiles_n = N / BN;
     const int tiles = ((max_rows + BM - 1) / BM) * tiles_n;
     // persistent blocks: one per CU slot (a multiple of 8), fewer when there are fewer tiles
-    const int slots = ctx->num_cus * ((BM * BN <= 128 * 128) ? 2 : 1);
+    const int slots = ctx->num_cus * (BM == 256 ? 1 : BM == 128 ? 2 : 4);
     const int grid = std::max(8, std::min(slots, (tiles + 7) & ~7) & ~7);
     ProfScope prof(ctx, prof_kind);
     hipLaunchKernelGGL((gemm_kernel<BM, BN, WM, WN, EPI>), dim3(grid), dim3(64 * WM * WN), smem, ctx->stream, A, W, bias,
@@ -414,7 +414,7 @@ int launch_gemm(leann_ctx *ctx, int prof_kind, const bf16_t *A, const bf16_t *W,
 template <int BM, int BN, int EPI>
 int gemm_allow_lds()
 {
-    constexpr int WM = 2, WN = (BM * BN <= 128 * 128) ? 2 : 4;
+    constexpr int WM = 2, WN = BN / 64;
     LEANN_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_kernel<BM, BN, WM, WN, EPI>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, gemm_smem_bytes<BM, BN, WM, WN>()));
     return LEANN_OK;
@@ -429,6 +429,8 @@ int enc_init_device()
     LEANN_TRY((gemm_allow_lds<256, 256, EPI_BIAS_GELU>()));
     LEANN_TRY((gemm_allow_lds<128, 128, EPI_BIAS>()));
     LEANN_TRY((gemm_allow_lds<128, 128, EPI_BIAS_GELU>()));
+    LEANN_TRY((gemm_allow_lds<64, 64, EPI_BIAS>()));
+    LEANN_TRY((gemm_allow_lds<64, 64, EPI_BIAS_GELU>()));
     LEANN_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(attention_kernel<8>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, AttCfg<8>::SMEM));
     return LEANN_OK;
@@ -467,6 +469,10 @@ int enc_forward(leann_ctx *ctx, const leann_chunks *chunks, const int64_t *ids_d
         return v ? atoi(v) : 256;
     }();
     const bool wide = tile_pref == 256 && d % 256 == 0 && F % 256 == 0;
+    static const int small_rows = [] {
+        const char *v = getenv("LEANN_GEMM_SMALL_ROWS");
+        return v ? atoi(v) : 2048;
+    }();
 
     for (int64_t s = 0; s < n; s += per_pass) {
         const int m = (int)((n - s < per_pass) ? n - s : per_pass);
@@ -475,6 +481,9 @@ int enc_forward(leann_ctx *ctx, const leann_chunks *chunks, const int64_t *ids_d
         // two per CU) is faster there (measured: +15 % at 32 chunks of up to 256 tokens, -6 % at 64).  Both tiles add
         // the K-slabs in the same order, so a row's result does not depend on the choice.
         const bool big = wide && max_rows > 8192;
+        // a pass of one query's flush (a dozen chunks) does not even fill the CUs with 128x128 tiles: 64x64 tiles
+        // (measured: faster up to 2048 padded rows, slower from 3072 on; LEANN_GEMM_SMALL_ROWS moves the limit)
+        const bool tiny = !big && max_rows <= small_rows && d % 64 == 0 && F % 64 == 0;
         const int32_t *T_dev = cu + m;
         {
             ProfScope prof(ctx, LEANN_PROF_ENC_OTHER);
@@ -497,7 +506,8 @@ int enc_forward(leann_ctx *ctx, const leann_chunks *chunks, const int64_t *ids_d
             const LayerWeights &w = ctx->layers[l];
 #define LEANN_GEMM(EPI, KIND, A_, W_, B_, O_, N_, K_)                                                               \
     LEANN_TRY((big ? launch_gemm<256, 256, EPI>(ctx, KIND, A_, W_, B_, O_, T_dev, max_rows, N_, K_)                   \
-                   : launch_gemm<128, 128, EPI>(ctx, KIND, A_, W_, B_, O_, T_dev, max_rows, N_, K_)))
+               : tiny ? launch_gemm<64, 64, EPI>(ctx, KIND, A_, W_, B_, O_, T_dev, max_rows, N_, K_)                   \
+                      : launch_gemm<128, 128, EPI>(ctx, KIND, A_, W_, B_, O_, T_dev, max_rows, N_, K_)))
             LEANN_GEMM(EPI_BIAS, LEANN_PROF_GEMM_QKV, x, w.wqkv, w.bqkv, qkv, 3 * d, d);
             {
                 ProfScope prof(ctx, LEANN_PROF_ATTENTION);

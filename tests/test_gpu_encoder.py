@@ -147,10 +147,11 @@ def test_small_shape_sample_matches_oracle(L, orc):
           (np.abs(got[ids] - want).max(), np.abs(got[ids] - want_bf).max()))
 
 
-def test_width_256_takes_the_large_tile_at_its_shortest_k(L, orc):
+def test_width_256_all_three_gemm_tiles(L, orc):
     """hidden = 256: the 256 x 256 GEMM tile with K = 256 (eight K-slabs, the fewest it is launched for: no
     full group of four before the tail) and K = 1024; ragged rows; against the oracle.  The same chunks embedded in
-    a pass small enough for the 128 x 128 tile give the same bits (both tiles add the K-slabs in one order)."""
+    passes small enough for the 128 x 128 and the 64 x 64 tile give the same bits (all tiles add the K-slabs in one
+    order)."""
     import torch
     cfg = dict(layers=3, hidden=256, heads=4, ffn=1024, vocab=2000, max_pos=128, ln_eps=1e-12)
     say("width-256 encoder, large and small GEMM tile")
@@ -161,10 +162,12 @@ def test_width_256_takes_the_large_tile_at_its_shortest_k(L, orc):
     try:
         t, l = to_dev(tokens), to_dev(lengths)
         got = L.leann_embed(ctx, t, l, hidden=256).cpu().numpy()            # 12800 padded rows: large tile
-        few = L.leann_embed(ctx, t, l, n_ids=32, hidden=256).cpu().numpy()  # 4096 padded rows: small tile
+        some = L.leann_embed(ctx, t, l, n_ids=48, hidden=256).cpu().numpy()  # 6144 padded rows: 128 x 128 tile
+        few = L.leann_embed(ctx, t, l, n_ids=16, hidden=256).cpu().numpy()   # 2048 padded rows: 64 x 64 tile
     finally:
         L.leann_destroy(ctx)
-    assert np.array_equal(got[:32], few)
+    assert np.array_equal(got[:48], some)
+    assert np.array_equal(got[:16], few)
     ids = np.array([0, 1, 2, 3, 50, 99], np.int64)
     e = orc.desc(**cfg)
     want = orc.embed(e, w, tokens, lengths, ids=ids)
