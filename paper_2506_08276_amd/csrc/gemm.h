@@ -46,7 +46,7 @@ constexpr int gemm_smem_bytes()
 template <int BM, int BN, int WM, int WN, int EPI>
 __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4) ? 2 : 1) void gemm_kernel(
     const bf16_t *__restrict__ A, const bf16_t *__restrict__ W, const float *__restrict__ bias,
-    bf16_t *__restrict__ out, const int32_t *__restrict__ T_dev, int N, int K, int tiles_n)
+    bf16_t *__restrict__ out, const int32_t *__restrict__ T_dev, int N, int K, int tiles_n, int gcols)
 {
     constexpr int BK = GEMM_BK;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -65,6 +65,9 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4) ? 2 : 1) void gemm_ker
     // else would hide them).  Blocks go round-robin to the 8 XCDs: block b sits on XCD b % 8.  At step j the
     // blocks of one XCD take a contiguous run of tiles (same A rows, all column tiles), so the A slab is reused out
     // of that XCD's L2 (measured: 2.3x fewer bytes fetched by the QKV GEMM than with the plain tile order).
+    // When W is larger than an XCD's L2 and the output is wide (FFN1), the host splits the column tiles into groups
+    // (gcols tiles each): an XCD then works with part of W only, which stays in its L2, at the price of reading A
+    // once per group.
     const int T = *T_dev;
     const int n_tiles = ((T + BM - 1) / BM) * tiles_n;
     const int per_xcd = (n_tiles + 7) >> 3;
@@ -146,13 +149,22 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4) ? 2 : 1) void gemm_ker
         SGB(0x008, 2 * TM * TN)                                                                          \
     }
 
-    // tile of this block at a step of its walk (uniform for the block); false when the walk is over
+    // tile of this block at a step of its walk (uniform for the block); false when the walk is over.  The logical
+    // order goes through the column tiles in groups of gcols: all row blocks for the first group, then for the
+    // next (gcols = tiles_n: plain row-major order).  An XCD's contiguous share then lies in one group, or two.
+    const int tiles_m = n_tiles / tiles_n;
 #define GEMM_TILE_AT(step_, ok_, tm_, tn_)                                                               \
     {                                                                                                    \
         const int in_xcd_ = (step_) * blocks_per_xcd + (int)(blockIdx.x >> 3);                           \
         const int logical_ = (int)(blockIdx.x & 7) * per_xcd + in_xcd_;                                  \
         ok_ = in_xcd_ < per_xcd && logical_ < n_tiles;                                                   \
-        if (ok_) { tm_ = logical_ / tiles_n; tn_ = logical_ % tiles_n; }                                 \
+        if (ok_) {                                                                                       \
+            const int g_ = logical_ / (tiles_m * gcols);                                                 \
+            const int r_ = logical_ - g_ * tiles_m * gcols;                                              \
+            const int cg_ = min(gcols, tiles_n - g_ * gcols);                                            \
+            tm_ = r_ / cg_;                                                                              \
+            tn_ = g_ * gcols + r_ % cg_;                                                                 \
+        }                                                                                                \
     }
     bool have;
     int tile_m = 0, tile_n = 0;
