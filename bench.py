@@ -25,7 +25,7 @@ PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak (published)
 # HBM-side bytes per valid token per GEMM launch (average of the QKV, O, FFN1, FFN2 launches), from the rocprofv3
 # FETCH_SIZE / WRITE_SIZE runs summarised in profiles/encoder_seq256_hbm_traffic.md (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0
 # after calibration against a 1 GiB copy); the algorithmic minimum is 6.15 KB.
-GEMM_TRAFFIC_BYTES_PER_TOKEN = 10.55e3
+GEMM_TRAFFIC_BYTES_PER_TOKEN = 8.96e3
 
 
 def log(*a):
