@@ -143,6 +143,10 @@ int leann_create(leann_ctx **out, const leann_encoder_desc *desc, const void *we
         if (hipGetDeviceProperties(&prop, device) == hipSuccess && prop.multiProcessorCount >= 8)
             ctx->num_cus = prop.multiProcessorCount;
     }
+    if (enc_ln_blocks_per_cu(&ctx->ln_blocks_per_cu) != LEANN_OK) {
+        leann_destroy(ctx);
+        return LEANN_EDEVICE;
+    }
     const size_t d = e.hidden, F = e.ffn, L = e.layers;
     const size_t n_emb = ((size_t)e.vocab + e.max_pos + 1) * d;
     size_t bf_bytes = up256(e.vocab * d * 2) + up256(e.max_pos * d * 2) + up256(d * 2) +

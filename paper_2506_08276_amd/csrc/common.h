@@ -50,6 +50,7 @@ struct leann_ctx {
     leann_encoder_desc desc;
     int device = 0;
     int num_cus = 256;
+    int ln_blocks_per_cu = 4;
     hipStream_t stream = nullptr;
     // weights
     DevBuf w_bf16, w_f32;
@@ -93,6 +94,7 @@ struct leann_pq {
 
 // Per-device set-up of each source file's kernels (LDS limits); called by leann_create with the device current.
 int enc_init_device();
+int enc_ln_blocks_per_cu(int *out);  // resident blocks of the LayerNorm kernel per CU on the current device
 int pq_init_device();
 int search_init_device();
 
