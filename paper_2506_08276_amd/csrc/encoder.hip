@@ -226,7 +226,10 @@ __global__ __launch_bounds__(256, NKT == 4 ? 3 : 2) void attention_kernel(const 
     bf16_t *Ks = reinterpret_cast<bf16_t *>(smem);  // [LP][64], 16-byte chunks XOR-swizzled by row
     bf16_t *Vt = Ks + AttCfg<NKT>::LP * 64;         // [64][VS]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int c = blockIdx.x, h = blockIdx.y;
+    // consecutive blocks are the heads of one chunk: they read adjacent 128-byte pieces of the same QKV rows at
+    // about the same time
+    const int H = d >> 6;
+    const int c = blockIdx.x / H, h = blockIdx.x % H;
     const int t0 = cu[c], L = cu[c + 1] - t0;
     if (L <= 0) return;
     const int nkt = (L + 31) >> 5;
@@ -552,10 +555,10 @@ int enc_forward(leann_ctx *ctx, const leann_chunks *chunks, const int64_t *ids_d
             {
                 ProfScope prof(ctx, LEANN_PROF_ATTENTION);
                 if (seq <= 128)
-                    hipLaunchKernelGGL(attention_kernel<4>, dim3(m, H), dim3(256), AttCfg<4>::SMEM, ctx->stream, qkv, cu,
+                    hipLaunchKernelGGL(attention_kernel<4>, dim3((unsigned)m * H), dim3(256), AttCfg<4>::SMEM, ctx->stream, qkv, cu,
                                        att, d, scale_log2e);
                 else
-                    hipLaunchKernelGGL(attention_kernel<8>, dim3(m, H), dim3(256), AttCfg<8>::SMEM, ctx->stream, qkv, cu,
+                    hipLaunchKernelGGL(attention_kernel<8>, dim3((unsigned)m * H), dim3(256), AttCfg<8>::SMEM, ctx->stream, qkv, cu,
                                        att, d, scale_log2e);
             }
             LEANN_GEMM(EPI_BIAS, LEANN_PROF_GEMM_O, att, w.wo, w.bo, delta, d, d);
