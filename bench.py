@@ -557,6 +557,7 @@ def main():
         "recall_at_3": rec, "target_recall": args.target_recall,
         "recomputed_chunks_per_query": recomputed_per_query,
         "hops_per_query": st["hops"] / args.nq, "adc_candidates_per_query": st["adc_candidates"] / args.nq,
+        "flushes_per_query": st["flushes"] / args.nq, "encoded_chunks_per_query": st["encoded_chunks"] / args.nq,
         "rounds": st["rounds"], "encoded_tokens_per_step": st["encoded_tokens"],
         "search_chunks_per_s": st["encoded_chunks"] / (dt / args.steps),
         "time_split_pct": {"encoder": 100.0 * enc_ms / all_ms if all_ms else None,
