@@ -52,11 +52,13 @@ def test_sampled_embeddings_and_adc_against_oracle(orc, world):
         assert np.all(np.abs(adc[i] - ref) <= 1e-4 * np.abs(ref))
 
 
-def test_search_properties_at_bench_configuration(world):
+@pytest.mark.parametrize("ef,alpha", [(64, 0.1), (80, 0.05)])
+def test_search_properties_at_bench_configuration(world, ef, alpha):
+    """(64, 0.1) is the search configuration's starting point, (80, 0.05) the operating point bench.py times."""
     w, L, torch = world, world["L"], world["torch"]
     nq, n = w["args"].nq, w["args"].n
-    say("search, bench parameters ef=64 alpha=0.1 batch=64")
-    ids, scores, st = search(w, w["queries"])
+    say(f"search, bench parameters ef={ef} alpha={alpha} batch=64")
+    ids, scores, st = search(w, w["queries"], ef=ef, alpha=alpha)
     assert ids.shape == (nq, 3) and bool(((ids >= 0) & (ids < n)).all())
     assert all(len(set(r.tolist())) == 3 for r in ids)
     assert bool((scores[:, :-1] >= scores[:, 1:]).all())
@@ -65,22 +67,22 @@ def test_search_properties_at_bench_configuration(world):
     assert float((scores - ref).abs().max()) <= 1e-5
     # recall against the exact top-3 over the stored embeddings (the bench's ground truth)
     recall = (ids.unsqueeze(2) == w["gt"].unsqueeze(1)).any(2).sum().item() / w["gt"].numel()
-    print(f"recall@3 at ef=64: {recall:.3f}; {st['recomputed_chunks'] / nq:.0f} recomputed and "
+    print(f"recall@3 at ef={ef}, alpha={alpha}: {recall:.3f}; {st['recomputed_chunks'] / nq:.0f} recomputed and "
           f"{st['encoded_chunks'] / nq:.0f} encoded chunks per query, {st['rounds']} rounds")
     assert recall >= 0.85
     assert 0 < st["encoded_chunks"] <= st["recomputed_chunks"] and st["hops"] >= nq
     # a query's answer does not depend on the rest of the call
     say("split call")
-    a, sa, _ = search(w, w["queries"][:40].contiguous())
-    b, sb, _ = search(w, w["queries"][40:].contiguous())
+    a, sa, _ = search(w, w["queries"][:40].contiguous(), ef=ef, alpha=alpha)
+    b, sb, _ = search(w, w["queries"][40:].contiguous(), ef=ef, alpha=alpha)
     assert torch.equal(torch.cat([a, b]), ids) and torch.equal(torch.cat([sa, sb]), scores)
     # recomputation equals reading the same embeddings from the stored-embedding table
     say("stored-embedding table covering every node")
     cache = (torch.arange(n, dtype=torch.int32, device="cuda"), w["emb"])
-    c_ids, c_scores, c_st = search(w, w["queries"], cache=cache)
+    c_ids, c_scores, c_st = search(w, w["queries"], ef=ef, alpha=alpha, cache=cache)
     assert torch.equal(c_ids, ids) and torch.equal(c_scores, scores)
     assert c_st["encoded_chunks"] == 0 and c_st["recomputed_chunks"] == st["recomputed_chunks"]
     # larger queue: recall does not drop, more work
-    ids2, _, st2 = search(w, w["queries"], ef=160)
+    ids2, _, st2 = search(w, w["queries"], ef=2 * ef + 32, alpha=alpha)
     recall2 = (ids2.unsqueeze(2) == w["gt"].unsqueeze(1)).any(2).sum().item() / w["gt"].numel()
     assert recall2 >= recall - 0.02 and st2["recomputed_chunks"] > st["recomputed_chunks"]
