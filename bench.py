@@ -253,8 +253,8 @@ def hub_cache_leg(L, torch, world, args, ef, qps_plain, ids_plain):
 
 
 def prune_ablation(args):
-    """--prune-ablation: Algorithm 3 on the device against the two naive ways to shrink a graph (Sec. 5, the ablation
-    on graph pruning): the original graph (every node may keep M edges), high-degree preserving pruning (top beta of
+    """--prune-ablation: Algorithm 3 on the device against the two naive ways to shrink a graph (Sec. 5 and the ablation
+    on graph pruning in Sec. 7.3): the original graph (every node may keep M edges), high-degree preserving pruning (top beta of
     the nodes by degree keep M, the others m), a uniformly smaller degree cap with about the same number of edges, and
     random removal of edges of the original graph down to the same count.  For each graph: recall@3 and recomputed
     chunks per query over an ef sweep (two-level search of the bench, exact scores read from the stored embeddings so
