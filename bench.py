@@ -47,7 +47,7 @@ def chunk_flops(cfg, lengths):
 def build_world(args, L, torch):
     import numpy as np
     import leann_inputs as li
-    cfg = dict(li.BASE)
+    cfg = dict(li.SMALL if getattr(args, "shape", "base") == "small" else li.BASE)
     seed = li.config_seed(3)
     dev = "cuda:0"
     t0 = time.time()
@@ -447,7 +447,7 @@ def main():
     ap.add_argument("--max-tokens", type=int, default=0, help="padded tokens per encoder pass (0 = library default)")
     ap.add_argument("--encoder-only", action="store_true", help="run only the seq-256 encoder batches (profiling aid)")
     ap.add_argument("--shape", choices=["base", "small"], default="base",
-                    help="with --encoder-only: BERT-base shape (12 x 768) or the 34 M-parameter 12 x 384 encoder")
+                    help="BERT-base shape (12 x 768) or the 34 M-parameter 12 x 384 encoder (a second throughput point)")
     ap.add_argument("--profile-pass", action="store_true", help="with --encoder-only: a single 2048-chunk batch")
     ap.add_argument("--adc-microbench", action="store_true", help="run only the stand-alone ADC scorer table")
     ap.add_argument("--sweep", action="store_true", help="re-rank ratio x batch x ef grid on the search workload")
@@ -550,7 +550,7 @@ def main():
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"search N={args.n} (config {3 if args.n == 100000 and args.seq == 128 else 'custom'}): "
-                               f"BERT-base-shape encoder seq {args.seq}, "
+                               f"{'12 x 384' if args.shape == 'small' else 'BERT-base-shape'} encoder seq {args.seq}, "
                                + ("pruned kNN graph 16/64" if args.graph == "fixture" else "Alg. 3 graph built on the device (16/64)")
                                + f", PQ 32 B, {args.nq} queries", "ef": ef, "k": args.k,
                    "rerank_ratio": args.rerank_ratio, "batch": args.batch, "n": args.n, "nq": args.nq},
@@ -567,7 +567,7 @@ def main():
         "roofline": {"bound": "mfma", "kernel": "gemm_kernel (QKV, O, FFN1, FFN2 launches)", "achieved": gemm_tflops,
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": gemm_tflops / PEAK_BF16_TFLOPS,
                      "traffic": GEMM_TRAFFIC_BYTES_PER_TOKEN * prof["tokens"] * cfg["layers"] * 4 / gemm_launches
-                     if gemm_launches else None, "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE/WRITE_SIZE, "
+                     if gemm_launches and args.shape == "base" else None, "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE/WRITE_SIZE, "
                      "calibrated, measured on the seq-256 encoder pass and scaled by tokens per launch)",
                      "avg_launch_ms": gemm_ms / gemm_launches if gemm_launches else None,
                      "launches": gemm_launches,
