@@ -503,13 +503,13 @@ int enc_forward(leann_ctx *ctx, const leann_chunks *chunks, const int64_t *ids_d
     int32_t *cu = (int32_t *)ctx->cu.p;
     int64_t *chunk_of = (int64_t *)ctx->enc_ids.p;
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)(d / H));
-    // 256x256 block tiles when every GEMM width allows it (LDS traffic per flop halves); LEANN_GEMM_TILE=128
-    // forces the small tile (tuning aid).
+    // 256x256 block tiles for large passes and output widths that are multiples of 256 (LDS traffic per flop
+    // halves); LEANN_GEMM_TILE=128 forces the small tile (tuning aid).
     static const int tile_pref = [] {
         const char *v = getenv("LEANN_GEMM_TILE");
         return v ? atoi(v) : 256;
     }();
-    const bool wide = tile_pref == 256 && d % 256 == 0 && F % 256 == 0;
+    const bool wide = tile_pref == 256;
     static const int small_rows = [] {
         const char *v = getenv("LEANN_GEMM_SMALL_ROWS");
         return v ? atoi(v) : 2048;
@@ -521,7 +521,7 @@ int enc_forward(leann_ctx *ctx, const leann_chunks *chunks, const int64_t *ids_d
         // a pass of a few thousand tokens has too few 256x256 tiles for the CUs: the 128x128 tile (four times the blocks,
         // two per CU) is faster there (measured: +15 % at 32 chunks of up to 256 tokens, -6 % at 64).  Both tiles add
         // the K-slabs in the same order, so a row's result does not depend on the choice.
-        const bool big = wide && max_rows > 8192;
+        const bool big = wide && max_rows > 8192;  // and, per GEMM, an output width that is a multiple of 256
         // a pass of one query's flush (a dozen chunks) does not even fill the CUs with 128x128 tiles: 64x64 tiles
         // (measured: faster up to 2048 padded rows, slower from 3072 on; LEANN_GEMM_SMALL_ROWS moves the limit)
         const bool tiny = !big && max_rows <= small_rows && d % 64 == 0 && F % 64 == 0;
@@ -548,7 +548,8 @@ int enc_forward(leann_ctx *ctx, const leann_chunks *chunks, const int64_t *ids_d
         for (int l = 0; l < e.layers; ++l) {
             const LayerWeights &w = ctx->layers[l];
 #define LEANN_GEMM(EPI, KIND, A_, W_, B_, O_, N_, K_)                                                               \
-    LEANN_TRY((big ? launch_gemm<256, 256, EPI>(ctx, KIND, A_, W_, B_, O_, T_dev, max_rows, N_, K_)                   \
+    LEANN_TRY((big && (N_) % 256 == 0 && (K_) >= 256                                                                \
+                   ? launch_gemm<256, 256, EPI>(ctx, KIND, A_, W_, B_, O_, T_dev, max_rows, N_, K_)                   \
                : tiny ? launch_gemm<64, 64, EPI>(ctx, KIND, A_, W_, B_, O_, T_dev, max_rows, N_, K_)                   \
                       : launch_gemm<128, 128, EPI>(ctx, KIND, A_, W_, B_, O_, T_dev, max_rows, N_, K_)))
             LEANN_GEMM(EPI_BIAS, LEANN_PROF_GEMM_QKV, x, w.wqkv, w.bqkv, qkv, 3 * d, d);
