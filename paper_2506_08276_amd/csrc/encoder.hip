@@ -92,31 +92,50 @@ __global__ __launch_bounds__(256) void embed_ln_kernel(const int32_t *__restrict
         if (lane == 0) atomicOr(err, 4);
         tok = 0;
     }
-    const int per = d >> 6;
-    float v[16];
+    // a lane owns 16-byte pieces (8 elements) j*64 + lane of the row, as in the residual LayerNorm below
+    const int pieces = d >> 3;
+    const bf16_t *te = tok_emb + (size_t)tok * d, *pe = pos_emb + (size_t)t * d;
+    float v[2][8];
     float s = 0.f;
 #pragma unroll
-    for (int j = 0; j < 16; ++j)
-        if (j < per) {
-            int c = j * 64 + lane;
-            v[j] = (float)tok_emb[(size_t)tok * d + c] + (float)pos_emb[(size_t)t * d + c] + (float)seg_emb[c];
-            s += v[j];
+    for (int j = 0; j < 2; ++j)
+        if (j * 64 + lane < pieces) {
+            const int c0 = (j * 64 + lane) * 8;
+            const bf16x8 a = *reinterpret_cast<const bf16x8 *>(te + c0);
+            const bf16x8 p = *reinterpret_cast<const bf16x8 *>(pe + c0);
+            const bf16x8 sg = *reinterpret_cast<const bf16x8 *>(seg_emb + c0);
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                v[j][i] = (float)a[i] + (float)p[i] + (float)sg[i];
+                s += v[j][i];
+            }
         }
     const float mean = wave_sum(s) / (float)d;
     float q = 0.f;
 #pragma unroll
-    for (int j = 0; j < 16; ++j)
-        if (j < per) {
-            float c = v[j] - mean;
-            q += c * c;
+    for (int j = 0; j < 2; ++j)
+        if (j * 64 + lane < pieces) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const float c = v[j][i] - mean;
+                q += c * c;
+            }
         }
     const float inv = 1.0f / sqrtf(wave_sum(q) / (float)d + eps);
     bf16_t *xr = x + (size_t)(row0 + t) * d;
 #pragma unroll
-    for (int j = 0; j < 16; ++j)
-        if (j < per) {
-            int c = j * 64 + lane;
-            xr[c] = (bf16_t)((v[j] - mean) * inv * g[c] + b[c]);
+    for (int j = 0; j < 2; ++j)
+        if (j * 64 + lane < pieces) {
+            const int c0 = (j * 64 + lane) * 8;
+            const f32x4 g0 = *reinterpret_cast<const f32x4 *>(g + c0), g1 = *reinterpret_cast<const f32x4 *>(g + c0 + 4);
+            const f32x4 b0 = *reinterpret_cast<const f32x4 *>(b + c0), b1 = *reinterpret_cast<const f32x4 *>(b + c0 + 4);
+            bf16x8 o;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                o[i] = (bf16_t)((v[j][i] - mean) * inv * g0[i] + b0[i]);
+                o[i + 4] = (bf16_t)((v[j][i + 4] - mean) * inv * g1[i] + b1[i]);
+            }
+            *reinterpret_cast<bf16x8 *>(xr + c0) = o;
         }
 }
 
@@ -381,12 +400,39 @@ __global__ __launch_bounds__(256, NKT == 4 ? 3 : 2) void attention_kernel(const 
 }
 
 // ------------------------------------------------------------------ masked mean pool + L2 normalise
+// One block per chunk.  Wave w sums rows w, w + 4, ... with 16-byte loads (a lane owns pieces j*64 + lane of a row, as
+// in the LayerNorm kernels); the four partial sums of a column are added in wave order, so the result does not depend
+// on anything but the chunk.
 __global__ __launch_bounds__(256) void pool_kernel(const bf16_t *__restrict__ x, const int32_t *__restrict__ cu, int d,
                                                    float *__restrict__ out)
 {
+    __shared__ float part[4][1024];
     __shared__ float red[256];
-    const int c = blockIdx.x, tid = threadIdx.x;
+    const int c = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int t0 = cu[c], L = cu[c + 1] - t0;
+    const int pieces = d >> 3;
+    float acc[2][8];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int i = 0; i < 8; ++i) acc[j][i] = 0.f;
+    for (int t = wave; t < L; t += 4) {
+        const bf16_t *xr = x + (size_t)(t0 + t) * d;
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            if (j * 64 + lane < pieces) {
+                const bf16x8 r = *reinterpret_cast<const bf16x8 *>(xr + (j * 64 + lane) * 8);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) acc[j][i] += (float)r[i];
+            }
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+        if (j * 64 + lane < pieces) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) part[wave][(j * 64 + lane) * 8 + i] = acc[j][i];
+        }
+    __syncthreads();
     float v[4] = {0.f, 0.f, 0.f, 0.f};
     float sq = 0.f;
     if (L > 0) {
@@ -394,9 +440,7 @@ __global__ __launch_bounds__(256) void pool_kernel(const bf16_t *__restrict__ x,
         for (int j = 0; j < 4; ++j) {
             const int col = tid + 256 * j;
             if (col < d) {
-                float s = 0.f;
-                for (int t = 0; t < L; ++t) s += (float)x[(size_t)(t0 + t) * d + col];
-                v[j] = s / (float)L;
+                v[j] = (((part[0][col] + part[1][col]) + part[2][col]) + part[3][col]) / (float)L;
                 sq += v[j] * v[j];
             }
         }
