@@ -510,7 +510,7 @@ def main():
             rec = recall_at_3(ids, world["gt"])
             log(f"ef={hi}: recall@3={rec:.3f}, {st['total_ms']:.0f} ms")
         if rec >= args.target_recall:
-            while hi - lo > max(4, hi // 16):
+            while hi - lo > max(1, hi // 64):
                 mid = (lo + hi) // 2
                 ids, _, st = run(mid)
                 r = recall_at_3(ids, world["gt"])
