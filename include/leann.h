@@ -176,6 +176,21 @@ int leann_adc(leann_ctx *ctx, const float *queries_dev, int64_t nq, const leann_
               const uint32_t *cand_ids_dev, int32_t nc, float *out_dev);
 
 /*
+ * leann_adc for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same kernels and same results as leann_adc; the
+ * per-query lookup tables live in a fixed array inside the library (4 MiB + 256 bytes per GPU, held
+ * until the process ends) instead of a grown workspace.  The call allocates nothing, records no
+ * memset and does not synchronise: the work is enqueued on the context's stream.
+ *   Limits: nq <= 128 and m_sub <= 32; anything larger -> LEANN_ECAPACITY, nothing enqueued.
+ *   A candidate id >= n is not reported through the status (that would need a synchronisation):
+ *   out_dev holds -inf at its position.
+ *   All calls on one GPU share the array: calls that overlap on one GPU (different streams or
+ *   contexts) race; calls on one stream are ordered and safe.
+ */
+int leann_adc_noalloc(leann_ctx *ctx, const float *queries_dev, int64_t nq, const leann_pq *pq,
+                      const uint32_t *cand_ids_dev, int32_t nc, float *out_dev);
+
+/*
  * Two-level search with dynamic batching (Algorithm 2, Sec. 4.1-4.2) for nq
  * independent queries, all stages on the device.
  * Per query: EQ (exact queue, size ef) starts with the entry point's exact score.

@@ -19,7 +19,7 @@ LEANN_F32, LEANN_BF16 = 0, 1
 STATUS = {0: "LEANN_OK", -1: "LEANN_EINVAL", -2: "LEANN_ENOMEM", -3: "LEANN_EDEVICE", -4: "LEANN_ESHAPE",
           -5: "LEANN_ECAPACITY"}
 EXPORTS = ["leann_last_error", "leann_create", "leann_destroy", "leann_embed", "leann_build_pq", "leann_pq_export",
-           "leann_pq_import", "leann_pq_wrap", "leann_pq_info", "leann_pq_free", "leann_adc", "leann_search",
+           "leann_pq_import", "leann_pq_wrap", "leann_pq_info", "leann_pq_free", "leann_adc", "leann_adc_noalloc", "leann_search",
            "leann_search_updates", "leann_build_graph", "leann_top_degree",
            "leann_set_limits", "leann_profile_begin", "leann_profile_end"]
 PROF_KINDS = ["gemm_qkv", "gemm_o", "gemm_ffn1", "gemm_ffn2", "attention", "layernorm", "enc_other", "traverse",
@@ -200,6 +200,18 @@ def leann_adc(ctx, queries, pq, cand_ids, out=None):
     if out is None:
         out = torch.empty((nq, nc), dtype=torch.float32, device=queries.device)
     _check(load_library().leann_adc(ctx, _ptr(queries), C.c_int64(nq), pq, _ptr(cand_ids), C.c_int32(nc), _ptr(out)))
+    return out
+
+
+def leann_adc_noalloc(ctx, queries, pq, cand_ids, out):
+    """leann_adc through the library's fixed workspace (no allocation, no synchronisation); `out` is required."""
+    _dev(queries, torch.float32, "queries")
+    _dev(cand_ids, torch.int32, "cand_ids")
+    _dev(out, torch.float32, "out")
+    nq, nc = cand_ids.shape
+    assert out.shape == (nq, nc)
+    _check(load_library().leann_adc_noalloc(ctx, _ptr(queries), C.c_int64(nq), pq, _ptr(cand_ids), C.c_int32(nc),
+                                            _ptr(out)))
     return out
 
 

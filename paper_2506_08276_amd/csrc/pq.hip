@@ -1,7 +1,9 @@
 // Product quantisation: training, encoding, per-query lookup tables and the stand-alone ADC scorer
-// (LEANN Sec. 3 offline stage "lightweight PQ table"; Alg. 2 "Dist(q, x~_v)").  256 centroids per subspace.
+// (LEANN Sec. 3 offline stage: the PQ table kept in place of the embeddings; Alg. 2: the approximate distance that
+// ranks new neighbours).  256 centroids per subspace.
 #include <math.h>
 
+#include <mutex>
 #include <vector>
 
 #include "common.h"
@@ -227,12 +229,39 @@ int alloc_pq(leann_ctx *ctx, int64_t n, int32_t d, int32_t m_sub, bool own_codes
     return LEANN_OK;
 }
 
+// ---- workspace of leann_adc_noalloc: a fixed device array instead of a grown allocation.
+// Layout: lookup tables fp32 [NOALLOC_MAX_QUERIES][m_sub][256] with m_sub * 256 * 4 <= NOALLOC_LUT_BYTES per query,
+// then one 256-byte slot whose first int is the kernel's bad-id flag.  Every GPU the library runs on holds its own
+// copy of the array until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; what kernels and copies get is the per-device address looked up below.
+constexpr int NOALLOC_MAX_QUERIES = 128;
+constexpr int NOALLOC_LUT_BYTES = 32 * KSUB * (int)sizeof(float);  // per query: up to 32 subspaces
+constexpr size_t NOALLOC_FLAG_OFFSET = (size_t)NOALLOC_MAX_QUERIES * NOALLOC_LUT_BYTES;
+static __device__ __align__(256) unsigned char scratch[NOALLOC_FLAG_OFFSET + 256];
+
+constexpr int NOALLOC_MAX_DEVICES = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[NOALLOC_MAX_DEVICES] = {};  // device address of `scratch` on each device, 0 = not looked up yet
+
+__global__ void clear_flag_kernel(int *flag) { *flag = 0; }
+
 }  // namespace
 
 int pq_init_device()
 {
     LEANN_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(adc_kernel),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024));
+    // once per device, with that device current (leann_create made it so): where this device keeps `scratch`
+    int dev = -1;
+    LEANN_HIP(hipGetDevice(&dev));
+    if (dev >= 0 && dev < NOALLOC_MAX_DEVICES) {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[dev]) {
+            void *ptr = nullptr;
+            LEANN_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+            g_scratch_ptr[dev] = ptr;
+        }
+    }
     return LEANN_OK;
 }
 
@@ -436,6 +465,40 @@ int leann_adc(leann_ctx *ctx, const float *queries_dev, int64_t nq, const leann_
         leann_set_error("leann_adc: candidate id outside [0, n)");
         return LEANN_EINVAL;
     }
+    return LEANN_OK;
+}
+
+int leann_adc_noalloc(leann_ctx *ctx, const float *queries_dev, int64_t nq, const leann_pq *pq,
+                      const uint32_t *cand_ids_dev, int32_t nc, float *out_dev)
+{
+    if (!ctx || !queries_dev || !pq || !cand_ids_dev || !out_dev || nq < 0 || nc < 0) {
+        leann_set_error("leann_adc_noalloc: null argument or negative count");
+        return LEANN_EINVAL;
+    }
+    const int smem = pq->m_sub * KSUB * (int)sizeof(float);
+    if (nq > NOALLOC_MAX_QUERIES || smem > NOALLOC_LUT_BYTES) {
+        leann_set_error("leann_adc_noalloc: %lld queries x %d subspaces exceed the fixed workspace (at most %d queries, "
+                        "%d subspaces); use leann_adc", (long long)nq, pq->m_sub, NOALLOC_MAX_QUERIES,
+                        NOALLOC_LUT_BYTES / (KSUB * (int)sizeof(float)));
+        return LEANN_ECAPACITY;
+    }
+    if (ctx->device < 0 || ctx->device >= NOALLOC_MAX_DEVICES || !g_scratch_ptr[ctx->device]) {
+        leann_set_error("leann_adc_noalloc: no fixed workspace was set up for device %d", ctx->device);
+        return LEANN_EDEVICE;
+    }
+    if (nq == 0 || nc == 0) return LEANN_OK;
+    LEANN_HIP(hipSetDevice(ctx->device));
+    unsigned char *base = static_cast<unsigned char *>(g_scratch_ptr[ctx->device]);
+    float *lut = reinterpret_cast<float *>(base);
+    int *flag = reinterpret_cast<int *>(base + NOALLOC_FLAG_OFFSET);
+    // the array keeps the last call's contents: the flag starts at zero (a kernel, not a memset, so that the call
+    // can be recorded into a graph); the tables are overwritten for exactly the queries that are read
+    hipLaunchKernelGGL(clear_flag_kernel, dim3(1), dim3(1), 0, ctx->stream, flag);
+    hipLaunchKernelGGL(lut_kernel, dim3((unsigned)nq, pq->m_sub), dim3(256), 0, ctx->stream, queries_dev, pq->d,
+                       pq->m_sub, pq->codebook, lut);
+    hipLaunchKernelGGL(adc_kernel, dim3((unsigned)nq, (nc + ADC_PER_BLOCK - 1) / ADC_PER_BLOCK), dim3(256), smem,
+                       ctx->stream, (const float *)lut, pq->codes, pq->n, pq->m_sub, cand_ids_dev, nc, out_dev, flag);
+    LEANN_HIP(hipGetLastError());
     return LEANN_OK;
 }
 
