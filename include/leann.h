@@ -96,7 +96,7 @@ typedef struct {
 
 /* Per-call totals over all queries of a leann_search call. */
 typedef struct {
-    int64_t hops;              /* exploration steps (Alg. 2 "read the closest unvisited node") */
+    int64_t hops;              /* exploration steps (Alg. 2: taking the best unvisited node of EQ) */
     int64_t adc_candidates;    /* neighbours scored with PQ */
     int64_t recomputed_chunks; /* exact scores taken (sum over queries, entry point included) */
     int64_t encoded_chunks;    /* chunks actually sent through the encoder (after sharing within a round) */
@@ -107,7 +107,9 @@ typedef struct {
     float encoder_ms, traverse_ms, total_ms; /* device time (HIP events) */
 } leann_search_stats;
 
-const char *leann_last_error(void);
+/* Message of the last error on the calling thread.  ctx is accepted for symmetry with the other calls and may be
+ * NULL (leann_create fails before a context exists); the string is per thread, not per context. */
+const char *leann_last_error(const leann_ctx *ctx);
 
 /*
  * Create a context holding the encoder weights.
@@ -127,7 +129,7 @@ int leann_create(leann_ctx **out, const leann_encoder_desc *desc, const void *we
 void leann_destroy(leann_ctx *ctx);
 
 /*
- * Embedding recomputation (Alg. 2 "Recompute embedding x_c"; Sec. 3 online stage).
+ * Embedding recomputation (Alg. 2, the recomputation step; Sec. 3 online stage).
  * For each requested chunk: x = LN(tok_emb[id_t] + pos_emb[t] + seg_emb), t < L;
  * per layer  x = LN(x + MHA(x) Wo + bo),  x = LN(x + GELU(x W1 + b1) W2 + b2)
  * with softmax over the L valid keys only; e = mean_t x_t;  e <- e / max(|e|, 1e-12).
@@ -141,7 +143,7 @@ int leann_embed(leann_ctx *ctx, const leann_chunks *chunks, const int64_t *ids_d
                 float *out_emb_dev);
 
 /*
- * Build the PQ table (Sec. 3 offline stage: "builds a lightweight PQ table").
+ * Build the PQ table of the offline stage (Sec. 3: the index keeps a small PQ table of all embeddings).
  * Splits d into m_sub contiguous sub-vectors; per subspace runs `iters` Lloyd
  * iterations with 256 centroids on min(n, 65536) rows chosen by a seeded
  * permutation (splitmix64 Fisher-Yates; the first 256 rows of it are the initial
@@ -150,7 +152,9 @@ int leann_embed(leann_ctx *ctx, const leann_chunks *chunks, const int64_t *ids_d
  */
 int leann_build_pq(leann_ctx *ctx, const float *emb_dev, int64_t n, int32_t d, int32_t m_sub, int32_t iters,
                    uint64_t seed, leann_pq **out);
-/* Copy codebook fp32[m_sub][256][d/m_sub] and codes u8[n][m_sub] to host buffers (either may be NULL). */
+/* The PQ table is one of the two things the index stores (Sec. 3 "Storage composition": graph + PQ codes); the
+ * calls below move it between the library and the caller.
+ * Copy codebook fp32[m_sub][256][d/m_sub] and codes u8[n][m_sub] to host buffers (either may be NULL). */
 int leann_pq_export(leann_ctx *ctx, const leann_pq *pq, float *codebook_host, uint8_t *codes_host);
 /* Make a PQ table from host copies of a codebook and codes. */
 int leann_pq_import(leann_ctx *ctx, const float *codebook_host, const uint8_t *codes_host, int64_t n, int32_t d,
@@ -163,8 +167,8 @@ int leann_pq_info(const leann_pq *pq, int64_t *n, int32_t *d, int32_t *m_sub);
 void leann_pq_free(leann_pq *pq);
 
 /*
- * Approximate scores (Alg. 2 "Insert (v, Dist(q, x~_v)) into AQ"), product
- * quantisation's asymmetric distance: for each query a lookup table
+ * Approximate scores (Alg. 2, the step that ranks a hop's new neighbours by their PQ distance to
+ * the query before they enter AQ), product quantisation's asymmetric distance: for each query a lookup table
  * lut[m][c] = -|q_m - codebook[m][c]|^2 is built (sub-vector summed in index order)
  * and out[i][j] = sum_m lut[m][codes[cand[i][j]][m]] in the fixed order m = 0..m_sub-1,
  * fp32: the negated squared distance between q and the decoded vector (larger is closer).
@@ -206,7 +210,8 @@ int leann_adc_noalloc(leann_ctx *ctx, const float *queries_dev, int64_t nq, cons
  * A query's result does not depend on nq or on the other queries of the call:
  * the encoder batches across queries, never changing a chunk's embedding.
  *   queries_dev fp32[nq][hidden]; out_ids_dev int64[nq][k]; out_scores_dev fp32[nq][k];
- *   cache: optional stored embeddings (NULL = none); stats_host: optional totals.
+ *   cache: optional stored embeddings (NULL = none; a slot_of entry >= rows -> LEANN_EINVAL);
+ *   stats_host: optional totals.
  * Errors: k < 1, k > ef, ef > 1024, rerank_ratio outside (0,1], batch < 1, entry >= n,
  * graph/chunk/PQ sizes that disagree -> LEANN_EINVAL / LEANN_ESHAPE; a neighbour id >= n
  * or a per-query queue overflow -> LEANN_EINVAL / LEANN_ECAPACITY after the run
@@ -249,7 +254,7 @@ int leann_build_graph(leann_ctx *ctx, const float *emb_dev, int64_t n, int32_t d
                       int32_t efC, int32_t M, int32_t m, int32_t batch, int32_t ramp, uint64_t *row_ptr_dev,
                       uint32_t *col_idx_dev, int64_t *n_edges_host);
 
-/* Algorithm 3, "nodes with the top beta% highest degrees": is_hub_dev[v] = 1 for the
+/* Algorithm 3's set V* of highest-degree nodes: is_hub_dev[v] = 1 for the
  * ceil(beta * n) nodes of largest out-degree in the CSR graph (ties: lower id), else 0.
  * Degrees above 4096 -> LEANN_ECAPACITY. */
 int leann_top_degree(leann_ctx *ctx, const uint64_t *row_ptr_dev, int64_t n, double beta, uint8_t *is_hub_dev);
@@ -257,6 +262,10 @@ int leann_top_degree(leann_ctx *ctx, const uint64_t *row_ptr_dev, int64_t n, dou
 /* Tuning knobs (all optional): largest number of tokens one encoder pass holds
  * (workspace size), and the per-query capacity of the approximate queue. */
 int leann_set_limits(leann_ctx *ctx, int64_t max_tokens_per_pass, int32_t aq_capacity);
+/* GEMM tile choice of the encoder (a tuning and test aid; results do not depend on it, every tile adds the K-slabs
+ * in the same order): large_tile 256 (default) or 128 = block tile for passes of more than 8192 padded rows
+ * (0 leaves it); small_rows = passes of at most this many padded rows use 64x64 tiles (default 2048). */
+int leann_set_gemm_tiles(leann_ctx *ctx, int32_t large_tile, int32_t small_rows);
 
 /*
  * Per-kernel device timing for the benchmark: between leann_profile_begin and leann_profile_end every kernel

@@ -21,7 +21,7 @@ STATUS = {0: "LEANN_OK", -1: "LEANN_EINVAL", -2: "LEANN_ENOMEM", -3: "LEANN_EDEV
 EXPORTS = ["leann_last_error", "leann_create", "leann_destroy", "leann_embed", "leann_build_pq", "leann_pq_export",
            "leann_pq_import", "leann_pq_wrap", "leann_pq_info", "leann_pq_free", "leann_adc", "leann_adc_noalloc", "leann_search",
            "leann_search_updates", "leann_build_graph", "leann_top_degree",
-           "leann_set_limits", "leann_profile_begin", "leann_profile_end"]
+           "leann_set_limits", "leann_set_gemm_tiles", "leann_profile_begin", "leann_profile_end"]
 PROF_KINDS = ["gemm_qkv", "gemm_o", "gemm_ffn1", "gemm_ffn2", "attention", "layernorm", "enc_other", "traverse",
               "collect", "score_insert", "lut", "adc"]
 
@@ -83,7 +83,7 @@ def load_library(path=LIB_PATH):
 
 def _check(rc):
     if rc != 0:
-        raise LeannError(rc, load_library().leann_last_error().decode())
+        raise LeannError(rc, load_library().leann_last_error(None).decode())
 
 
 def _ptr(t):
@@ -117,6 +117,10 @@ def leann_destroy(ctx):
 
 def leann_set_limits(ctx, max_tokens_per_pass=0, aq_capacity=0):
     _check(load_library().leann_set_limits(ctx, C.c_int64(max_tokens_per_pass), C.c_int32(aq_capacity)))
+
+
+def leann_set_gemm_tiles(ctx, large_tile=0, small_rows=2048):
+    _check(load_library().leann_set_gemm_tiles(ctx, C.c_int32(large_tile), C.c_int32(small_rows)))
 
 
 def _chunks(tokens, lengths):

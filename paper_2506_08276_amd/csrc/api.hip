@@ -80,33 +80,40 @@ __global__ void bf16_to_f32_kernel(const bf16_t *__restrict__ in, float *__restr
 
 size_t up256(size_t v) { return (v + 255) & ~(size_t)255; }
 
-// copies `count` packed source elements starting at element `src_off` into an own bf16 / fp32 buffer
-void to_bf16(leann_ctx *ctx, const void *src, int dtype, size_t src_off, size_t count, bf16_t *dst)
+// copies `count` packed source elements starting at element `src_off` into an own bf16 / fp32 buffer; a failed
+// copy is remembered in *status (the first one wins)
+void to_bf16(hipError_t *status, leann_ctx *ctx, const void *src, int dtype, size_t src_off, size_t count, bf16_t *dst)
 {
     const unsigned grid = (unsigned)std::min<size_t>((count + 255) / 256, 4096);
     if (dtype == LEANN_F32)
         hipLaunchKernelGGL(f32_to_bf16_kernel, dim3(grid), dim3(256), 0, ctx->stream, (const float *)src + src_off, dst,
                            count);
     else
-        (void)hipMemcpyAsync(dst, (const bf16_t *)src + src_off, count * sizeof(bf16_t), hipMemcpyDeviceToDevice,
-                             ctx->stream);
+    {
+        const hipError_t e = hipMemcpyAsync(dst, (const bf16_t *)src + src_off, count * sizeof(bf16_t),
+                                            hipMemcpyDeviceToDevice, ctx->stream);
+        if (*status == hipSuccess) *status = e;
+    }
 }
-void to_f32(leann_ctx *ctx, const void *src, int dtype, size_t src_off, size_t count, float *dst)
+void to_f32(hipError_t *status, leann_ctx *ctx, const void *src, int dtype, size_t src_off, size_t count, float *dst)
 {
     const unsigned grid = (unsigned)std::min<size_t>((count + 255) / 256, 4096);
     if (dtype == LEANN_BF16)
         hipLaunchKernelGGL(bf16_to_f32_kernel, dim3(grid), dim3(256), 0, ctx->stream, (const bf16_t *)src + src_off, dst,
                            count);
     else
-        (void)hipMemcpyAsync(dst, (const float *)src + src_off, count * sizeof(float), hipMemcpyDeviceToDevice,
-                             ctx->stream);
+    {
+        const hipError_t e = hipMemcpyAsync(dst, (const float *)src + src_off, count * sizeof(float),
+                                            hipMemcpyDeviceToDevice, ctx->stream);
+        if (*status == hipSuccess) *status = e;
+    }
 }
 
 }  // namespace
 
 extern "C" {
 
-const char *leann_last_error(void) { return g_err; }
+const char *leann_last_error(const leann_ctx *) { return g_err; }
 
 int leann_create(leann_ctx **out, const leann_encoder_desc *desc, const void *weights_dev, int weight_dtype, int device,
                  void *hip_stream)
@@ -158,16 +165,17 @@ int leann_create(leann_ctx **out, const leann_encoder_desc *desc, const void *we
     }
     char *pb = (char *)ctx->w_bf16.p, *pf = (char *)ctx->w_f32.p;
     size_t so = 0;  // element offset in the packed source
+    hipError_t copy_rc = hipSuccess;
     auto mat = [&](size_t count) {
         bf16_t *dst = (bf16_t *)pb;
-        to_bf16(ctx, weights_dev, weight_dtype, so, count, dst);
+        to_bf16(&copy_rc, ctx, weights_dev, weight_dtype, so, count, dst);
         pb += up256(count * 2);
         so += count;
         return (const bf16_t *)dst;
     };
     auto vec = [&](size_t count) {
         float *dst = (float *)pf;
-        to_f32(ctx, weights_dev, weight_dtype, so, count, dst);
+        to_f32(&copy_rc, ctx, weights_dev, weight_dtype, so, count, dst);
         pf += up256(count * 4);
         so += count;
         return (const float *)dst;
@@ -195,6 +203,7 @@ int leann_create(leann_ctx **out, const leann_encoder_desc *desc, const void *we
         w.be2 = vec(d);
     }
     hipError_t rc = hipGetLastError();
+    if (rc == hipSuccess) rc = copy_rc;
     if (rc == hipSuccess) rc = hipStreamSynchronize(ctx->stream);
     if (rc != hipSuccess) {
         leann_set_error("copying the weights failed: %s", hipGetErrorString(rc));
@@ -231,6 +240,17 @@ int leann_set_limits(leann_ctx *ctx, int64_t max_tokens_per_pass, int32_t aq_cap
     }
     if (max_tokens_per_pass > 0) ctx->max_tokens = std::min<int64_t>(max_tokens_per_pass, (int64_t)1 << 22);
     if (aq_capacity > 0) ctx->aq_capacity = aq_capacity;
+    return LEANN_OK;
+}
+
+int leann_set_gemm_tiles(leann_ctx *ctx, int32_t large_tile, int32_t small_rows)
+{
+    if (!ctx || (large_tile != 0 && large_tile != 128 && large_tile != 256) || small_rows < 0) {
+        leann_set_error("leann_set_gemm_tiles: null context, a large tile other than 128 / 256, or a negative row limit");
+        return LEANN_EINVAL;
+    }
+    if (large_tile) ctx->gemm_large_tile = large_tile;
+    ctx->gemm_small_rows = small_rows;
     return LEANN_OK;
 }
 
@@ -349,8 +369,8 @@ int leann_search_updates(leann_ctx *ctx, const float *queries_dev, int64_t nq, c
                         (long long)graph->n, (long long)chunks->n, (long long)pq->n, pq->d, ctx->desc.hidden);
         return LEANN_ESHAPE;
     }
-    if (cache && (!cache->slot_of || !cache->emb)) {
-        leann_set_error("leann_search: embedding cache with null pointers");
+    if (cache && (!cache->slot_of || !cache->emb || cache->rows < 0 || cache->rows > 0x7fffffffll)) {
+        leann_set_error("leann_search: embedding cache with null pointers or a row count outside 0..2^31-1");
         return LEANN_EINVAL;
     }
     if (updates && (updates->buffer_n < 0 || updates->buffer_n > (1 << 24) ||

@@ -60,6 +60,8 @@ struct leann_ctx {
     // limits
     int64_t max_tokens = 1048576;  // padded tokens per encoder pass (workspaces: about 17 KB per token at BERT-base width)
     int32_t aq_capacity = 0;  // 0 = derive from ef and graph
+    int32_t gemm_large_tile = 256;   // 256: 256x256 block tiles for large passes; 128: never (leann_set_gemm_tiles)
+    int32_t gemm_small_rows = 2048;  // passes of at most this many padded rows use 64x64 tiles
     // encoder workspace
     DevBuf x, qkv, att, delta, hid, cu, len, meta, enc_ids;
     // search workspace

@@ -1,12 +1,10 @@
-// Encoder forward pass for embedding recomputation (LEANN Alg. 2 "Recompute embedding x_c"; Sec. 3 online
+// Encoder forward pass for embedding recomputation (LEANN Alg. 2, the recomputation step; Sec. 3 online
 // stage), written for gfx950: bf16 MFMA GEMMs with LDS-staged, swizzled tiles, an MFMA attention kernel
 // working on ragged (token-packed) batches, and fp32 LayerNorm / pooling.
 //
 // Tokens of all chunks of a pass are packed back to back (no padding rows): chunk i owns rows
 // cu[i] .. cu[i+1] of every activation matrix.  The number of valid rows T is only known on the device,
 // so grids are sized for the worst case and blocks beyond T leave at once.
-#include <stdlib.h>
-
 #include <algorithm>
 
 #include "common.h"
@@ -548,16 +546,9 @@ int enc_forward(leann_ctx *ctx, const leann_chunks *chunks, const int64_t *ids_d
     int64_t *chunk_of = (int64_t *)ctx->enc_ids.p;
     const float scale_log2e = 1.4426950408889634f / sqrtf((float)(d / H));
     // 256x256 block tiles for large passes and output widths that are multiples of 256 (LDS traffic per flop
-    // halves); LEANN_GEMM_TILE=128 forces the small tile (tuning aid).
-    static const int tile_pref = [] {
-        const char *v = getenv("LEANN_GEMM_TILE");
-        return v ? atoi(v) : 256;
-    }();
-    const bool wide = tile_pref == 256;
-    static const int small_rows = [] {
-        const char *v = getenv("LEANN_GEMM_SMALL_ROWS");
-        return v ? atoi(v) : 2048;
-    }();
+    // halves); leann_set_gemm_tiles can force the small tile and move the row limit of the 64x64 tile.
+    const bool wide = ctx->gemm_large_tile == 256;
+    const int small_rows = ctx->gemm_small_rows;
 
     for (int64_t s = 0; s < n; s += per_pass) {
         const int m = (int)((n - s < per_pass) ? n - s : per_pass);
@@ -567,7 +558,7 @@ int enc_forward(leann_ctx *ctx, const leann_chunks *chunks, const int64_t *ids_d
         // the K-slabs in the same order, so a row's result does not depend on the choice.
         const bool big = wide && max_rows > 8192;  // and, per GEMM, an output width that is a multiple of 256
         // a pass of one query's flush (a dozen chunks) does not even fill the CUs with 128x128 tiles: 64x64 tiles
-        // (measured: faster up to 2048 padded rows, slower from 3072 on; LEANN_GEMM_SMALL_ROWS moves the limit)
+        // (measured: faster up to 2048 padded rows, slower from 3072 on; leann_set_gemm_tiles moves the limit)
         const bool tiny = !big && max_rows <= small_rows && d % 64 == 0 && F % 64 == 0;
         const int32_t *T_dev = cu + m;
         {

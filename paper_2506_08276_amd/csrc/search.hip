@@ -40,7 +40,7 @@ struct SearchState {
 };
 
 enum { CTR_HOPS = 0, CTR_ADC, CTR_RECOMP, CTR_FLUSH, CTR_PENDING, CTR_NENC, CTR_ERR, CTR_TOKENS, CTR_MAXDEG, CTR_HITS, CTR_COUNT };
-enum { ERR_BAD_NEIGHBOUR = 1, ERR_AQ_OVERFLOW = 2, ERR_P_OVERFLOW = 4 };
+enum { ERR_BAD_NEIGHBOUR = 1, ERR_AQ_OVERFLOW = 2, ERR_P_OVERFLOW = 4, ERR_BAD_SLOT = 8 };
 
 __device__ inline bool better(float sa, uint32_t ia, float sb, uint32_t ib) { return sa > sb || (sa == sb && ia < ib); }
 
@@ -133,7 +133,7 @@ __global__ __launch_bounds__(64) void traverse_kernel(SearchState s, const uint6
     uint32_t *pend = s.pend + (size_t)q * s.pcap;
     int hops = 0, adc = 0, err = 0;
     while (n_pend < batch) {
-        // Alg. 2: read the closest unvisited node u of EQ, mark it visited
+        // Alg. 2: u = the best node of EQ that has not been expanded yet; it is marked visited
         float bs = -INFINITY;
         uint32_t bid = 0xffffffffu;
         int bpos = -1;
@@ -241,19 +241,24 @@ __global__ __launch_bounds__(64) void traverse_kernel(SearchState s, const uint6
 // not depend on its batch, so every query still sees exactly the scores it would compute alone.
 constexpr int NO_OWNER = 0x7f7f7f7f;  // the fill byte 0x7f makes hipMemsetAsync usable
 
-__global__ __launch_bounds__(64) void claim_kernel(SearchState s, const int32_t *__restrict__ slot_of)
+// slot_of entries >= cache_rows would send score_insert_kernel outside the stored table: they are reported
+// (ERR_BAD_SLOT) and the host ends the search before anything reads through them.
+__global__ __launch_bounds__(64) void claim_kernel(SearchState s, const int32_t *__restrict__ slot_of, int64_t cache_rows)
 {
     const int q = blockIdx.x;
     const int np = s.n_pend[q];
     int hits = 0;
+    bool bad = false;
     for (int j = threadIdx.x; j < np; j += 64) {
         const uint32_t c = s.pend[(size_t)q * s.pcap + j];
         if (slot_of && slot_of[c] >= 0) {
+            bad |= slot_of[c] >= cache_rows;
             ++hits;
             continue;
         }
         atomicMin(&s.owner[c], q * s.pcap + j);
     }
+    if (bad) atomicOr((unsigned long long *)&s.counters[CTR_ERR], (unsigned long long)ERR_BAD_SLOT);
     if (slot_of) {
         for (int o = 32; o; o >>= 1) hits += __shfl_xor(hits, o);
         if (threadIdx.x == 0 && hits) atomicAdd((unsigned long long *)&s.counters[CTR_HITS], (unsigned long long)hits);
@@ -550,7 +555,12 @@ int search_run(leann_ctx *ctx, const float *queries_dev, int64_t nq, const leann
         return LEANN_ESHAPE;
     }
 
-    std::vector<hipEvent_t> evs;
+    struct Events : std::vector<hipEvent_t> {  // destroyed on every way out of this function
+        ~Events()
+        {
+            for (hipEvent_t e : *this) (void)hipEventDestroy(e);
+        }
+    } evs;
     auto mark = [&]() -> int {
         hipEvent_t e;
         LEANN_HIP(hipEventCreate(&e));
@@ -578,7 +588,7 @@ int search_run(leann_ctx *ctx, const float *queries_dev, int64_t nq, const leann
             {
                 ProfScope prof(ctx, LEANN_PROF_COLLECT);
                 const int32_t *slot_of = cache ? cache->slot_of : nullptr;
-                hipLaunchKernelGGL(claim_kernel, dim3(g), dim3(64), 0, st, s, slot_of);
+                hipLaunchKernelGGL(claim_kernel, dim3(g), dim3(64), 0, st, s, slot_of, cache ? cache->rows : 0);
                 hipLaunchKernelGGL(collect_kernel, dim3(1), dim3(1024), 0, st, s, g, slot_of);
                 hipLaunchKernelGGL(resolve_kernel, dim3(g), dim3(64), 0, st, s, slot_of);
             }
@@ -586,9 +596,10 @@ int search_run(leann_ctx *ctx, const float *queries_dev, int64_t nq, const leann
             LEANN_TRY(mark());
             LEANN_HIP(hipStreamSynchronize(st));
             if (h_ctr[CTR_ERR]) {
-                rc = (h_ctr[CTR_ERR] & ERR_BAD_NEIGHBOUR) ? LEANN_EINVAL : LEANN_ECAPACITY;
-                leann_set_error(rc == LEANN_EINVAL ? "graph holds a neighbour id >= n"
-                                                   : "a per-query queue outgrew its capacity (see leann_set_limits)");
+                rc = (h_ctr[CTR_ERR] & (ERR_BAD_NEIGHBOUR | ERR_BAD_SLOT)) ? LEANN_EINVAL : LEANN_ECAPACITY;
+                leann_set_error((h_ctr[CTR_ERR] & ERR_BAD_NEIGHBOUR) ? "graph holds a neighbour id >= n"
+                                : (h_ctr[CTR_ERR] & ERR_BAD_SLOT) ? "embedding cache: slot_of holds a row >= rows"
+                                : "a per-query queue outgrew its capacity (see leann_set_limits)");
                 break;
             }
             if (h_ctr[CTR_PENDING] == 0) {
@@ -666,6 +677,5 @@ int search_run(leann_ctx *ctx, const float *queries_dev, int64_t nq, const leann
         stats->traverse_ms = trav;
         stats->encoder_ms = total - trav;
     }
-    for (hipEvent_t e : evs) (void)hipEventDestroy(e);
     return rc;
 }

@@ -29,7 +29,7 @@ def test_library_exports_every_declared_symbol():
         assert hasattr(lib, name), name
     assert sorted(L.EXPORTS) == declared_symbols()
     lib.leann_last_error.restype = ctypes.c_char_p
-    assert lib.leann_last_error() is not None
+    assert lib.leann_last_error(None) is not None
 
 
 def test_binding_fails_loudly_without_library(tmp_path, monkeypatch):

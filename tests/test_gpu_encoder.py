@@ -108,7 +108,11 @@ def test_base_shape_sample_matches_oracle(L, orc):
     lengths[:5] = [1, 33, 64, 200, 256]
     ctx = L.leann_create(cfg, to_dev(w).to(torch.bfloat16))  # bf16 weight upload path
     try:
-        got = L.leann_embed(ctx, to_dev(tokens), to_dev(lengths), hidden=768).cpu().numpy()
+        got = L.leann_embed(ctx, to_dev(tokens), to_dev(lengths), hidden=768).cpu().numpy()  # 10240 padded rows: 256 x 256 tiles
+        L.leann_set_gemm_tiles(ctx, 128, 0)  # the same pass through 128 x 128 tiles: the same bits
+        assert np.array_equal(L.leann_embed(ctx, to_dev(tokens), to_dev(lengths), hidden=768).cpu().numpy(), got)
+        with pytest.raises(L.LeannError):
+            L.leann_set_gemm_tiles(ctx, 192, 0)
     finally:
         L.leann_destroy(ctx)
     ids = np.array([0, 1, 2, 3, 4, 17], np.int64)

@@ -33,7 +33,6 @@ def world(L, orc):
     w["t"], w["l"] = to_dev(w["tokens"]), to_dev(w["lengths"])
     w["q"] = to_dev(w["queries"])
     w["full_cache"] = (to_dev(np.arange(w["n"], dtype=np.int32)), to_dev(w["emb"]))
-    w["emb_bf16"] = orc.embed(w["desc"], w["w"], w["tokens"], w["lengths"], precision=1)
     yield w
     L.leann_pq_free(w["pq"])
     L.leann_destroy(ctx)
@@ -60,7 +59,14 @@ def test_search_logic_exact_with_stored_embeddings(L, orc, world, ef, k, alpha, 
         for j in range(k):
             if min(ls[j] - ls[j + 1], ls[j + 1] - ls[j + 2]) > 4e-6:
                 assert ids[qi][j] == r["ids"][j], (qi, j, ids[qi], r["ids"])
-        assert sorted(ids[qi]) == sorted(r["ids"]) or ls[k] - ls[k + 1] <= 4e-6 or k > 20
+        # the returned set: the same ids, unless the oracle's k-th and (k+1)-th best of everything it scored
+        # exactly (its log) lie within that rounding, in which case those two may trade places at the boundary
+        allsc = np.sort(r["log_scores"].astype(np.float64))[::-1]
+        boundary_tie = len(allsc) > k and allsc[k - 1] - allsc[k] <= 4e-6
+        if not boundary_tie:
+            assert sorted(ids[qi]) == sorted(r["ids"]), (qi, ids[qi], r["ids"])
+        else:
+            assert len(set(ids[qi]) ^ set(r["ids"])) <= 2, (qi, ids[qi], r["ids"])
         np.testing.assert_allclose(scores[qi], r["scores"], atol=2e-6)
     for key, okey in (("hops", "hops"), ("adc_candidates", "adc_candidates"), ("recomputed_chunks", "recomputed"),
                       ("flushes", "flushes")):
@@ -180,45 +186,63 @@ def decided_ranks(log_scores, k, gap=1e-3):
     return [j for j in range(k) if (j == 0 or ls[j - 1] - ls[j] > gap) and ls[j] - ls[j + 1] > gap]
 
 
-def full_path_case(L, orc, w, ctx, pq, graph, t, l, q, ef, k, alpha, batch, label):
+def full_path_case(L, orc, w, ctx, pq, graph, t, l, q, ef, k, alpha, batch, label, plain_rule):
+    """Full path (bf16 recomputation on the device) against the fp32 oracle.
+
+    plain_rule: every rank the oracle's gaps decide (more than 1e-3 to both neighbours) must hold the oracle's id.
+    Otherwise (the nearly collinear cloud of config 1) a decided rank is compared only if the oracle's own search,
+    run over the embeddings the device computed, also returns the oracle's id there: a rank that fails this has
+    been moved by the embeddings' 2e-2 precision through a fork of the trajectory at a near-tie somewhere along
+    the way, not by the search; such ranks are printed.  In both cases the device's result must equal, id for id,
+    the oracle's search over the device's own embeddings."""
     say(f"{label}: full path ef={ef} k={k} alpha={alpha} batch={batch}")
     ids, scores, st = L.leann_search(ctx, q, graph, pq, t, l, ef, k, alpha, batch)
     ids, scores = ids.cpu().numpy(), scores.cpu().numpy()
     runs = oracle_runs(orc, w, w["queries"], w["emb"], ef, k, alpha, batch)
-    # second oracle run in the kernel's storage precision: a rank is compared only if this change of precision
-    # does not move the oracle's own answer (the search is a heuristic whose trajectory can fork at a near-tie
-    # anywhere along the way, not only at the output)
-    runs_bf = oracle_runs(orc, w, w["queries"], w["emb_bf16"], ef, k, alpha, batch)
     gpu_emb = L.leann_embed(ctx, t, l, hidden=w["cfg"]["hidden"]).cpu().numpy()
     assert np.abs(gpu_emb - w["emb"]).max() <= 2e-2
+    runs_dev = oracle_runs(orc, w, w["queries"], gpu_emb, ef, k, alpha, batch)
     decided = agree = full = 0
+    excluded = []
     for qi, r in enumerate(runs):
         # the returned exact scores are <q, e_c> of the embeddings leann_embed gives for the same chunks
         np.testing.assert_allclose(scores[qi], gpu_emb[ids[qi]] @ w["queries"][qi], atol=1e-5)
         assert len(set(ids[qi])) == k
-        ranks = [j for j in decided_ranks(r["log_scores"], k) if runs_bf[qi]["ids"][j] == r["ids"][j]]
+        # Alg. 2 on the device = Alg. 2 of the oracle on the same exact scores (up to summation order)
+        rd = runs_dev[qi]
+        lsd = np.concatenate([[np.inf], rd["scores"].astype(np.float64), [-np.inf]])
+        for j in range(k):
+            if min(lsd[j] - lsd[j + 1], lsd[j + 1] - lsd[j + 2]) > 4e-6:
+                assert ids[qi][j] == rd["ids"][j], (label, "device embeddings", qi, j, ids[qi], rd["ids"])
+        ranks = decided_ranks(r["log_scores"], k)
+        if not plain_rule:
+            kept = [j for j in ranks if rd["ids"][j] == r["ids"][j]]
+            excluded += [(qi, j) for j in ranks if j not in kept]
+            ranks = kept
         decided += len(ranks)
         for j in ranks:
             assert ids[qi][j] == r["ids"][j], (label, qi, j, ids[qi], r["ids"], np.sort(r["log_scores"])[::-1][:k + 1])
         agree += sum(int(a == b) for a, b in zip(ids[qi], r["ids"]))
         full += list(ids[qi]) == list(r["ids"])
     nq = len(runs)
-    print(f"{label}: {decided}/{nq * k} ranks decided (gap > 1e-3, stable under bf16 storage) and all equal; {agree}/{nq * k} ranks and "
-          f"{full}/{nq} whole results equal to the fp32 oracle's; stats {st}")
+    print(f"{label}: {decided}/{nq * k} ranks decided (gap > 1e-3) and all equal; {agree}/{nq * k} ranks and "
+          f"{full}/{nq} whole results equal to the fp32 oracle's; decided ranks left out (query, rank): {excluded}; stats {st}")
     assert 0 < st["encoded_chunks"] <= st["recomputed_chunks"]  # chunks shared by queries in a round are encoded once
     return decided
 
 
 def test_config1_full_path_against_oracle(L, orc, world):
-    """Config 1 with on-device recomputation (bf16 encoder): ids agree with the fp32 oracle at every rank the
-    oracle's score gaps (> 1e-3 on both sides) decide.  Random-init embeddings of uniform tokens are nearly
-    collinear, so few ranks are decided here; the topic-structured variant below has many."""
+    """Config 1 with on-device recomputation (bf16 encoder).  Random-init embeddings of uniform tokens are nearly
+    collinear (pairwise cosine 0.96-0.985): few ranks are decided by a 1e-3 gap and a near-tie along the way can
+    fork the trajectory, so decided ranks are compared where the oracle's search over the device's embeddings
+    keeps the oracle's id; the topic-structured variant below asserts the plain gap rule."""
     w = world
-    full_path_case(L, orc, w, w["ctx"], w["pq"], w["graph"], w["t"], w["l"], w["q"], 32, 3, 0.2, 32, "config 1")
+    full_path_case(L, orc, w, w["ctx"], w["pq"], w["graph"], w["t"], w["l"], w["q"], 32, 3, 0.2, 32, "config 1", plain_rule=False)
 
 
 def test_structured_tiny_full_path_against_oracle(L, orc):
-    """Same shapes as config 1, chunks from the topic-mixture generator: neighbour gaps of a few 1e-3."""
+    """Same shapes as config 1, chunks from the topic-mixture generator: neighbour gaps of a few 1e-3.  The plain
+    rule: ids identical wherever the oracle's score gap exceeds 1e-3."""
     cfg = li.TINY
     seed = li.config_seed(1) + 100
     wts = li.encoder_weights(cfg, seed)
@@ -233,14 +257,15 @@ def test_structured_tiny_full_path_against_oracle(L, orc):
     row_ptr, col_idx = li.to_csr(nbr)
     cb, _ = orc.pq_train(emb, 16, 10, seed + 4)
     codes = orc.pq_encode(emb, cb)
-    w = dict(cfg=cfg, emb=emb, emb_bf16=orc.embed(e, wts, tokens, lengths, precision=1), queries=queries, row_ptr=row_ptr, col_idx=col_idx, entry=entry, cb=cb, codes=codes)
+    w = dict(cfg=cfg, emb=emb, queries=queries, row_ptr=row_ptr, col_idx=col_idx, entry=entry, cb=cb, codes=codes)
     ctx = L.leann_create(cfg, to_dev(wts))
     pq = L.leann_pq_import(ctx, cb, codes)
     try:
         total = 0
         for ef, k, alpha, batch in ((32, 3, 0.2, 32), (64, 3, 0.5, 8)):
             total += full_path_case(L, orc, w, ctx, pq, (to_dev(row_ptr), to_dev(col_idx), entry), to_dev(tokens),
-                                    to_dev(lengths), to_dev(queries), ef, k, alpha, batch, "structured tiny")
+                                    to_dev(lengths), to_dev(queries), ef, k, alpha, batch, "structured tiny",
+                                    plain_rule=True)
         assert total >= 30  # the comparison is not vacuous
         hits = 0
         ids, _, _ = L.leann_search(ctx, to_dev(queries), (to_dev(row_ptr), to_dev(col_idx), entry), pq, to_dev(tokens),
@@ -301,6 +326,10 @@ def test_unreachable_padding_and_argument_checks(L, world):
         L.leann_search(w["ctx"], w["q"][:1].contiguous(), (to_dev(row_ptr), to_dev(bad_col), 0), pq, t, l, 4, 3, 1.0, 2)
     with pytest.raises(L.LeannError):  # entry point outside the graph
         L.leann_search(w["ctx"], w["q"][:1].contiguous(), (to_dev(row_ptr), to_dev(col_idx), 6), pq, t, l, 4, 3, 1.0, 2)
+    with pytest.raises(L.LeannError) as ei:  # stored-embedding table: a slot beyond its rows
+        bad_cache = (to_dev(np.array([0, 7, 2, 3, 4, 5], np.int32)), to_dev(w["emb"][:6]))
+        L.leann_search(w["ctx"], w["q"][:1].contiguous(), graph, pq, t, l, 4, 3, 1.0, 2, cache=bad_cache)
+    assert ei.value.status == -1
     ids0, _, st0 = L.leann_search(w["ctx"], w["q"][:0].contiguous(), graph, pq, t, l, 4, 3, 1.0, 2)
     assert ids0.shape == (0, 3) and st0["hops"] == 0
     L.leann_pq_free(pq)
