@@ -287,6 +287,26 @@ typedef struct {
 int leann_profile_begin(leann_ctx *ctx);
 int leann_profile_end(leann_ctx *ctx, leann_profile *out_host);
 
+/*
+ * Measured denominator for the encoder's roofline (benchmark hook, not on the search path): the rate this GPU
+ * sustains on nothing but independent bf16 MFMA 32x32x16 instructions (8 accumulators per wave, the GEMM's wave
+ * tile), `launches` launches of blocks_per_cu (1 or 2) blocks of four waves per compute unit, `iters` rounds each.
+ * operand_kind: 0 zeros, 1 values near one, 2 random sign / exponent in [2^-4, 2) / mantissa.
+ * tflops_host receives TFLOP/s over the timed launches (HIP events on the context's stream, after three warm-up
+ * launches), ms_host (optional) the average launch duration.  Allocates and frees its buffers; synchronises.
+ */
+int leann_bench_mfma(leann_ctx *ctx, int32_t operand_kind, int32_t blocks_per_cu, int32_t iters, int32_t launches,
+                     double *tflops_host, double *ms_host);
+
+/*
+ * Measured ceiling of the ADC scorer's access pattern (benchmark hook): 67 108 864 gathers per launch of uniformly
+ * random 32-byte rows from table_dev (u8[table_rows][32], device, caller-owned), nothing else.  rows_per_s_host
+ * receives rows per second over `launches` timed launches after one warm-up launch, ms_host (optional) the average
+ * launch duration.  Allocates and frees 0.27 GB of ids; synchronises.
+ */
+int leann_bench_gather(leann_ctx *ctx, const uint8_t *table_dev, int64_t table_rows, int32_t launches,
+                       double *rows_per_s_host, double *ms_host);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,7 @@ STATUS = {0: "LEANN_OK", -1: "LEANN_EINVAL", -2: "LEANN_ENOMEM", -3: "LEANN_EDEV
 EXPORTS = ["leann_last_error", "leann_create", "leann_destroy", "leann_embed", "leann_build_pq", "leann_pq_export",
            "leann_pq_import", "leann_pq_wrap", "leann_pq_info", "leann_pq_free", "leann_adc", "leann_adc_noalloc", "leann_search",
            "leann_search_updates", "leann_build_graph", "leann_top_degree",
-           "leann_set_limits", "leann_set_gemm_tiles", "leann_profile_begin", "leann_profile_end"]
+           "leann_set_limits", "leann_set_gemm_tiles", "leann_profile_begin", "leann_profile_end", "leann_bench_mfma", "leann_bench_gather"]
 PROF_KINDS = ["gemm_qkv", "gemm_o", "gemm_ffn1", "gemm_ffn2", "attention", "layernorm", "enc_other", "traverse",
               "collect", "score_insert", "lut", "adc"]
 
@@ -315,3 +315,21 @@ def leann_profile_end(ctx):
     _check(load_library().leann_profile_end(ctx, C.byref(p)))
     return {"ms": {k: p.ms[i] for i, k in enumerate(PROF_KINDS)},
             "launches": {k: p.launches[i] for i, k in enumerate(PROF_KINDS)}, "tokens": p.tokens}
+
+
+def leann_bench_mfma(ctx, operand_kind, blocks_per_cu=2, iters=4000, launches=40):
+    """(TFLOP/s, ms per launch) of a loop of independent bf16 MFMAs; operand_kind 0 zeros, 1 near one, 2 random bits."""
+    tf, ms = C.c_double(), C.c_double()
+    _check(load_library().leann_bench_mfma(ctx, C.c_int32(operand_kind), C.c_int32(blocks_per_cu), C.c_int32(iters),
+                                           C.c_int32(launches), C.byref(tf), C.byref(ms)))
+    return tf.value, ms.value
+
+
+def leann_bench_gather(ctx, table, launches=5):
+    """(rows/s, ms per launch) of uniformly random 32-byte row gathers from `table` (uint8 CUDA tensor [rows][32])."""
+    _dev(table, torch.uint8, "table")
+    assert table.dim() == 2 and table.shape[1] == 32
+    rps, ms = C.c_double(), C.c_double()
+    _check(load_library().leann_bench_gather(ctx, _ptr(table), C.c_int64(table.shape[0]), C.c_int32(launches),
+                                             C.byref(rps), C.byref(ms)))
+    return rps.value, ms.value

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libleann.so")
-SOURCES = ["api.hip", "encoder.hip", "pq.hip", "search.hip", "build.hip"]
+SOURCES = ["api.hip", "encoder.hip", "pq.hip", "search.hip", "build.hip", "peak.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Xclang", "-target-feature", "-Xclang",
          "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 

@@ -226,11 +226,17 @@ __global__ __launch_bounds__(256) void ln_kernel(const bf16_t *__restrict__ delt
 // blocks per CU), 8 for up to 256.
 template <int NKT>
 struct AttCfg {
-    static constexpr int LP = NKT * 32;           // padded key capacity
-    static constexpr int VS = LP + 4;             // V^T row pitch (bf16): conflict-free 8-byte fragment reads
-    static constexpr int KV_BYTES = (LP * 64 + 64 * VS) * (int)sizeof(bf16_t);
+    static constexpr int LP = NKT * 32;           // padded key capacity = V^T row pitch (bf16)
+    static constexpr int KV_BYTES = (LP * 64 + 64 * LP) * (int)sizeof(bf16_t);
     static constexpr int SMEM = KV_BYTES + 4 * 16 * 128;  // plus, per wave, 16 output rows of 64 bf16
 };
+
+// V^T in LDS: row = output dimension (64 of them), LP keys per row in 16-byte groups of eight.  Inside a group of 16
+// keys the order follows the MFMA operand slots of P^T (a lane of half h holds, in slots 0..7, keys 4h + 0..3 and
+// 8 + 4h + 0..3): stored position 16j + 8h + slot, so that a lane's operand is one 16-byte read.  The group index is
+// XORed with a function of the row: the 16 rows that one pass of a 16-byte read serves, and the (chunk, half) pairs
+// that one pass of the staging stores serves, then fall into 16 different bank groups (no bank conflicts either way).
+__device__ inline int vt_swizzle(int row) { return (row & 15) ^ (((row >> 4) & 3) << 1); }
 
 template <int NKT>
 __global__ __launch_bounds__(256, NKT == 4 ? 3 : 2) void attention_kernel(const bf16_t *__restrict__ qkv,
@@ -238,10 +244,10 @@ __global__ __launch_bounds__(256, NKT == 4 ? 3 : 2) void attention_kernel(const 
                                                                           bf16_t *__restrict__ out, int d,
                                                                           float scale_log2e)
 {
-    constexpr int VS = AttCfg<NKT>::VS;
+    constexpr int LP = AttCfg<NKT>::LP;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     bf16_t *Ks = reinterpret_cast<bf16_t *>(smem);  // [LP][64], 16-byte chunks XOR-swizzled by row
-    bf16_t *Vt = Ks + AttCfg<NKT>::LP * 64;         // [64][VS]
+    bf16_t *Vt = Ks + LP * 64;                      // [64][LP], see vt_swizzle
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     // consecutive blocks are the heads of one chunk: they read adjacent 128-byte pieces of the same QKV rows at
     // about the same time
@@ -264,25 +270,44 @@ __global__ __launch_bounds__(256, NKT == 4 ? 3 : 2) void attention_kernel(const 
 #pragma unroll
         for (int s = 0; s < 4; ++s) qf[s] = *reinterpret_cast<const bf16x8 *>(qp + s * 16 + half * 8);
     }
-    // K rows as they are; V transposed, two keys per 4-byte LDS store.  Keys >= L are zero.
-    for (int idx = tid; idx < Lp * 4; idx += 256) {
-        const int kp = idx >> 3, ch = idx & 7, key = kp * 2;
-        u32x4 k0 = {0, 0, 0, 0}, k1 = {0, 0, 0, 0}, v0 = {0, 0, 0, 0}, v1 = {0, 0, 0, 0};
-        if (key < L) {
-            k0 = *reinterpret_cast<const u32x4 *>(kbase + (size_t)key * ld + ch * 8);
-            v0 = *reinterpret_cast<const u32x4 *>(vbase + (size_t)key * ld + ch * 8);
-        }
-        if (key + 1 < L) {
-            k1 = *reinterpret_cast<const u32x4 *>(kbase + (size_t)(key + 1) * ld + ch * 8);
-            v1 = *reinterpret_cast<const u32x4 *>(vbase + (size_t)(key + 1) * ld + ch * 8);
-        }
-        *reinterpret_cast<u32x4 *>(Ks + key * 64 + ((ch ^ ((key >> 1) & 7)) << 3)) = k0;
-        *reinterpret_cast<u32x4 *>(Ks + (key + 1) * 64 + ((ch ^ (((key + 1) >> 1) & 7)) << 3)) = k1;
-        uint32_t *vt32 = reinterpret_cast<uint32_t *>(Vt);
+    // Staging.  All global loads of the thread are issued before the first LDS store.  Keys >= L are zero.
+    // V: thread (j16, hf, ch) takes the eight keys 16 j16 + 4 hf + {0..3, 8..11} of the 16-byte chunk ch (eight
+    // output dimensions) and writes, per dimension, the eight keys as one 16-byte group.  Eight adjacent lanes read
+    // one whole 128-byte piece of a V row.
+    // K: rows as they are, 16-byte chunk ch of row key at position ch ^ ((key >> 1) & 7).
+    {
+        const int ch = tid & 7, hf = (tid >> 3) & 1, j16 = tid >> 4;
+        const bool v_on = j16 * 16 < Lp;
+        u32x4 vv[8], kk[NKT];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const uint32_t a = (v0[i >> 1] >> (16 * (i & 1))) & 0xffffu, b = (v1[i >> 1] >> (16 * (i & 1))) & 0xffffu;
-            vt32[((ch * 8 + i) * VS + key) >> 1] = a | (b << 16);
+        for (int r = 0; r < 8; ++r) {
+            const int key = j16 * 16 + 4 * hf + (r & 3) + 8 * (r >> 2);
+            vv[r] = u32x4{0, 0, 0, 0};
+            if (v_on && key < L) vv[r] = *reinterpret_cast<const u32x4 *>(vbase + (size_t)key * ld + ch * 8);
+        }
+#pragma unroll
+        for (int r = 0; r < NKT; ++r) {
+            const int key = r * 32 + (tid >> 3);
+            kk[r] = u32x4{0, 0, 0, 0};
+            if (key < L) kk[r] = *reinterpret_cast<const u32x4 *>(kbase + (size_t)key * ld + ch * 8);
+        }
+#pragma unroll
+        for (int r = 0; r < NKT; ++r) {
+            const int key = r * 32 + (tid >> 3);
+            if (key < Lp) *reinterpret_cast<u32x4 *>(Ks + key * 64 + ((ch ^ ((key >> 1) & 7)) << 3)) = kk[r];
+        }
+        if (v_on) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {  // output dimension ch * 8 + i: element i of each of the eight key rows
+                u32x4 o;
+#pragma unroll
+                for (int w = 0; w < 4; ++w) {
+                    const uint32_t a = vv[2 * w][i >> 1], b = vv[2 * w + 1][i >> 1];
+                    o[w] = (i & 1) ? ((a >> 16) | (b & 0xffff0000u)) : ((a & 0xffffu) | (b << 16));
+                }
+                const int row = ch * 8 + i;
+                *reinterpret_cast<u32x4 *>(Vt + row * LP + (((2 * j16 + hf) ^ vt_swizzle(row)) << 3)) = o;
+            }
         }
     }
     __syncthreads();
@@ -309,7 +334,11 @@ __global__ __launch_bounds__(256, NKT == 4 ? 3 : 2) void attention_kernel(const 
                 }
             }
         }
-        // lane owns query column l32 and keys 32t + 8(r/4) + 4*half + r%4; only the last tile can hold keys >= L
+        // lane owns query column l32 and keys 32t + 8(r/4) + 4*half + r%4; only the last tile can hold keys >= L.
+        // The bound is re-read per query block (the empty statement hides that it does not change): hoisted out of
+        // the loop, the 128 comparison results of the unrolled tiles would be kept in scalar registers and spilled.
+        int l_cmp = L - 4 * half;
+        asm volatile("" : "+v"(l_cmp));
         float mx = -INFINITY;
 #pragma unroll
         for (int t = 0; t < NKT; ++t)
@@ -317,7 +346,7 @@ __global__ __launch_bounds__(256, NKT == 4 ? 3 : 2) void attention_kernel(const 
                 if (t == nkt - 1) {
 #pragma unroll
                     for (int r = 0; r < 16; ++r)
-                        if (t * 32 + 8 * (r >> 2) + 4 * half + (r & 3) >= L) sc[t][r] = -INFINITY;
+                        if (t * 32 + 8 * (r >> 2) + (r & 3) >= l_cmp) sc[t][r] = -INFINITY;
                 }
 #pragma unroll
                 for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sc[t][r]);
@@ -350,13 +379,11 @@ __global__ __launch_bounds__(256, NKT == 4 ? 3 : 2) void attention_kernel(const 
                     bf16x8 pf;
 #pragma unroll
                     for (int i = 0; i < 8; ++i) pf[i] = (bf16_t)sc[t][8 * u + i];
-                    const int k0 = t * 32 + u * 16 + 4 * half;  // slots 0..3 -> keys k0..k0+3, slots 4..7 -> k0+8..k0+11
+                    const int pg = 4 * t + 2 * u + half;  // the lane's group: slots 0..3 = keys 32t + 16u + 4 half + 0..3, slots 4..7 = those + 8
 #pragma unroll
                     for (int dt = 0; dt < 2; ++dt) {
-                        const bf16_t *vr = Vt + (dt * 32 + l32) * VS + k0;
-                        bf16x4 lo = *reinterpret_cast<const bf16x4 *>(vr);
-                        bf16x4 hi = *reinterpret_cast<const bf16x4 *>(vr + 8);
-                        bf16x8 vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                        const int row = dt * 32 + l32;
+                        const bf16x8 vf = *reinterpret_cast<const bf16x8 *>(Vt + row * LP + ((pg ^ vt_swizzle(row)) << 3));
                         oacc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, oacc[dt], 0, 0, 0);
                     }
                 }

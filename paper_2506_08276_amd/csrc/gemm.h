@@ -191,20 +191,30 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4) ? 2 : 1) void gemm_ker
     GEMM_TILE_AT(step + 1, have_next, next_m, next_n)
     const auto ag_next = GEMM_RSRC(A + (size_t)next_m * BM * K, BM);
     const auto wg_next = GEMM_RSRC(W + (size_t)next_n * BN * K, BN);
-    f32x16 acc[TM][TN];
-#pragma unroll
-    for (int mi = 0; mi < TM; ++mi)
-#pragma unroll
-        for (int ni = 0; ni < TN; ++ni)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[mi][ni][r] = 0.f;
-
     // Slabs 0..3 of this tile are in the four register sets.  Steady state of the K loop at iteration 0: slabs 0 and
     // 1 in the ring, slabs 2, 3, 4 in sets 1, 2, 3, set 0 free.
     bf16x8 af0[TM], bf0[TN], af1[TM], bf1[TN];
     wbias[lane] = bnext;
     GEMM_SSTORE(ra0, rb0, 0)
     GEMM_SSTORE(ra1, rb1, 1)
+    // The accumulators start at the bias instead of zero (the sum over K is added on top in the matrix pipe), so the
+    // epilogue has no additions and no bias reads left: it costs as many register moves here as clearing did.  A
+    // lane owns, in registers 4g..4g+3 of accumulator (mi, ni), the columns ni*32 + 8g + 4*(lane/32) + 0..3 of the
+    // wave's 64; LDS serves a wave's accesses in order, so the reads see this wave's own store above.
+    f32x16 acc[TM][TN];
+    {
+        const float *bq = wbias + 4 * (lane >> 5);
+#pragma unroll
+        for (int ni = 0; ni < TN; ++ni)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const f32x4 bv = *reinterpret_cast<const f32x4 *>(bq + ni * 32 + 8 * g);  // one address per half-wave: a broadcast
+#pragma unroll
+                for (int mi = 0; mi < TM; ++mi)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) acc[mi][ni][4 * g + i] = bv[i];
+            }
+    }
 #pragma unroll
     for (int i = 0; i < ACH; ++i) { ra1[i] = ra2[i]; ra2[i] = ra3[i]; }
 #pragma unroll
@@ -243,7 +253,7 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4) ? 2 : 1) void gemm_ker
     __syncthreads();  // every wave is done with the operand stages
     constexpr int WCOLS = BN / WN;
     static_assert(WCOLS == 64, "the epilogue's staging layout is written for 64 output columns per wave");
-    unsigned char *stg = smem + wave * 32 * 128;
+    unsigned char *stg = smem + wave * (2 * 32 * 128);  // two slices per wave, used in turn
     const int col0 = tile_n * BN + wn * WCOLS;
     const int row0 = tile_m * BM + wm * (BM / WM);
     // What the epilogue derives from the lane is computed here, per tile, instead of occupying registers through the
@@ -252,35 +262,33 @@ __global__ __launch_bounds__(64 * WM * WN, (WM * WN <= 4) ? 2 : 1) void gemm_ker
     asm volatile("" : "+v"(lane_e));
     const int half = lane_e >> 5, l32 = lane_e & 31;
     const int wswz = ((l32 & 7) << 1) | ((l32 >> 3) & 1);
-    const float *bp = wbias + 4 * half;
     // write-out: a wave-wide access covers 8 rows of eight 16-byte chunks.  The output is read by a later kernel
     // only: streaming stores keep it from displacing the operand slabs in L2 (measured: 3-7% per GEMM).
     const int orow = lane_e >> 3, och = lane_e & 7;
 #pragma unroll
     for (int mi = 0; mi < TM; ++mi) {
+        unsigned char *sl = stg + (mi & 1) * (32 * 128);  // the other slice than the previous 32 rows: their reads may still be on their way
 #pragma unroll
         for (int ni = 0; ni < TN; ++ni)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const f32x4 bv = *reinterpret_cast<const f32x4 *>(bp + ni * 32 + 8 * g);  // one address per half-wave: a broadcast
                 bf16x4 o4;
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
-                    const float v = acc[mi][ni][4 * g + i] + bv[i];
+                    const float v = acc[mi][ni][4 * g + i];  // the bias is in the sum already
                     o4[i] = (bf16_t)(EPI == EPI_BIAS_GELU ? gelu_erf(v) : v);
                 }
                 const int u = ni * 8 + 2 * g + half;
-                *reinterpret_cast<bf16x4 *>(stg + l32 * 128 + ((u ^ wswz) << 3)) = o4;
+                *reinterpret_cast<bf16x4 *>(sl + l32 * 128 + ((u ^ wswz) << 3)) = o4;
             }
         __builtin_amdgcn_wave_barrier();  // LDS serves a wave's accesses in order: the reads below see the writes
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int lr = j * 8 + orow;
-            u32x4 v = *reinterpret_cast<const u32x4 *>(stg + lr * 128 + ((och ^ orow) << 4));
+            u32x4 v = *reinterpret_cast<const u32x4 *>(sl + lr * 128 + ((och ^ orow) << 4));
             if (j & 1) v = u32x4{v[2], v[3], v[0], v[1]};  // rows 8..15 and 24..31 hold the halves of a chunk swapped
             __builtin_nontemporal_store(v, reinterpret_cast<u32x4 *>(out + (size_t)(row0 + mi * 32 + lr) * N + col0 + och * 8));
         }
-        __builtin_amdgcn_wave_barrier();
     }
     __syncthreads();  // the staging slices are operand stages again for the next tile
     if (!have_next) break;

@@ -119,75 +119,117 @@ __global__ __launch_bounds__(256) void lut_kernel(const float *__restrict__ quer
     lut[((size_t)q * m_sub + m) * KSUB + c] = -s;
 }
 
-// out[q][j] = sum_m lut[q][m][codes[cand[q][j]][m]], m ascending.  grid (nq, ceil(nc / 2048)), 256 threads;
-// the query's table sits in LDS.  A thread owns up to 8 candidates: all their ids, then all their code rows
-// are requested before the first lookup, so that the random row gathers overlap instead of queueing up.
-constexpr int ADC_PER_BLOCK = 2048, ADC_PER_THREAD = ADC_PER_BLOCK / 256;
+// out[q][j] = sum_m lut[q][m][codes[cand[q][j]][m]], m ascending.  grid (nq, parts), 256 threads; the query's table
+// sits in LDS and serves the block's whole share of the candidates (`per_block`, a multiple of 2048): the 32 KB table
+// load is paid once per block, not once per 2048 candidates.  A thread owns 8 candidates per round: all their ids,
+// then all their code rows are requested before the first lookup, so that the random row gathers overlap instead of
+// queueing up; the ids of the next round are fetched while the current round's lookups run.
+constexpr int ADC_PER_ROUND = 2048, ADC_PER_THREAD = ADC_PER_ROUND / 256;
 
 __global__ __launch_bounds__(256) void adc_kernel(const float *__restrict__ lut, const uint8_t *__restrict__ codes,
                                                   int64_t n, int m_sub, const uint32_t *__restrict__ cand, int nc,
-                                                  float *__restrict__ out, int *__restrict__ err)
+                                                  int per_block, float *__restrict__ out, int *__restrict__ err)
 {
     extern __shared__ float tab[];  // [m_sub][256]
     const int q = blockIdx.x;
-    const int j0 = blockIdx.y * ADC_PER_BLOCK + threadIdx.x;
+    const int beg = blockIdx.y * per_block, end = min(nc, beg + per_block);
+    if (beg >= end) return;
+    const uint32_t *cq = cand + (size_t)q * nc;
+    float *oq = out + (size_t)q * nc;
     uint32_t v[ADC_PER_THREAD];
 #pragma unroll
     for (int i = 0; i < ADC_PER_THREAD; ++i) {
-        const int j = j0 + i * 256;
-        v[i] = j < nc ? cand[(size_t)q * nc + j] : 0xffffffffu;
+        const int j = beg + threadIdx.x + i * 256;
+        v[i] = j < end ? cq[j] : 0xffffffffu;
     }
     const float4 *src = reinterpret_cast<const float4 *>(lut + (size_t)q * m_sub * KSUB);
     for (int i = threadIdx.x; i < m_sub * KSUB / 4; i += 256) reinterpret_cast<float4 *>(tab)[i] = src[i];
+    bool bad = false;
     if (m_sub == 32) {  // 32-byte rows: both halves of every row in flight before any lookup
-        u32x4 c0[ADC_PER_THREAD], c1[ADC_PER_THREAD];
+        for (int j0 = beg + threadIdx.x; j0 < end + threadIdx.x; j0 += ADC_PER_ROUND) {
+            u32x4 c0[ADC_PER_THREAD], c1[ADC_PER_THREAD];
+            bool ok[ADC_PER_THREAD];
 #pragma unroll
-        for (int i = 0; i < ADC_PER_THREAD; ++i) {
-            const uint8_t *code = codes + (size_t)(v[i] < n ? v[i] : 0) * 32;
-            c0[i] = *reinterpret_cast<const u32x4 *>(code);
-            c1[i] = *reinterpret_cast<const u32x4 *>(code + 16);
-        }
-        __syncthreads();
-#pragma unroll
-        for (int i = 0; i < ADC_PER_THREAD; ++i) {
-            const int j = j0 + i * 256;
-            if (j >= nc) continue;
-            float s = 0.f;
-#pragma unroll
-            for (int m = 0; m < 16; ++m) s += tab[m * KSUB + ((c0[i][m >> 2] >> (8 * (m & 3))) & 255u)];
-#pragma unroll
-            for (int m = 0; m < 16; ++m) s += tab[(16 + m) * KSUB + ((c1[i][m >> 2] >> (8 * (m & 3))) & 255u)];
-            if (v[i] >= n) {
-                atomicOr(err, 1);
-                s = -INFINITY;
+            for (int i = 0; i < ADC_PER_THREAD; ++i) {
+                ok[i] = v[i] < n;
+                const uint8_t *code = codes + (size_t)(ok[i] ? v[i] : 0) * 32;
+                c0[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(code));
+                c1[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(code + 16));
             }
-            out[(size_t)q * nc + j] = s;
+#pragma unroll
+            for (int i = 0; i < ADC_PER_THREAD; ++i) {  // ids of the next round
+                const int j = j0 + ADC_PER_ROUND + i * 256;
+                v[i] = j < end ? cq[j] : 0xffffffffu;
+            }
+            if (j0 < beg + ADC_PER_ROUND) __syncthreads();  // first round: the table is complete (uniform condition)
+#pragma unroll
+            for (int i = 0; i < ADC_PER_THREAD; ++i) {
+                const int j = j0 + i * 256;
+                if (j >= end) continue;
+                // all 32 table entries are requested before the first addition: the sum itself is a chain of
+                // dependent additions in subspace order, and a lookup issued only when its turn in the chain comes
+                // would pay the LDS latency 32 times over
+                float e0[16], e1[16];
+#pragma unroll
+                for (int m = 0; m < 16; ++m) e0[m] = tab[m * KSUB + ((c0[i][m >> 2] >> (8 * (m & 3))) & 255u)];
+#pragma unroll
+                for (int m = 0; m < 16; ++m) e1[m] = tab[(16 + m) * KSUB + ((c1[i][m >> 2] >> (8 * (m & 3))) & 255u)];
+                float s = 0.f;
+#pragma unroll
+                for (int m = 0; m < 16; ++m) s += e0[m];
+#pragma unroll
+                for (int m = 0; m < 16; ++m) s += e1[m];
+                if (!ok[i]) {
+                    bad = true;
+                    s = -INFINITY;
+                }
+                __builtin_nontemporal_store(s, oq + j);
+            }
         }
+        if (bad) atomicOr(err, 1);
         return;
     }
     __syncthreads();
+    for (int j0 = beg + threadIdx.x; j0 < end + threadIdx.x; j0 += ADC_PER_ROUND) {
 #pragma unroll
-    for (int i = 0; i < ADC_PER_THREAD; ++i) {
-        const int j = j0 + i * 256;
-        if (j >= nc) continue;
-        float s = -INFINITY;
-        if (v[i] < n) {
-            const uint8_t *code = codes + (size_t)v[i] * m_sub;
-            s = 0.f;
-            if ((m_sub & 15) == 0) {
-                for (int m0 = 0; m0 < m_sub; m0 += 16) {
-                    const u32x4 w = *reinterpret_cast<const u32x4 *>(code + m0);
+        for (int i = 0; i < ADC_PER_THREAD; ++i) {
+            const int j = j0 + i * 256;
+            if (j >= end) continue;
+            const uint32_t id = cq[j];
+            float s = -INFINITY;
+            if (id < n) {
+                const uint8_t *code = codes + (size_t)id * m_sub;
+                s = 0.f;
+                if ((m_sub & 15) == 0) {
+                    for (int m0 = 0; m0 < m_sub; m0 += 16) {
+                        const u32x4 w = *reinterpret_cast<const u32x4 *>(code + m0);
 #pragma unroll
-                    for (int m = 0; m < 16; ++m) s += tab[(m0 + m) * KSUB + ((w[m >> 2] >> (8 * (m & 3))) & 255u)];
+                        for (int m = 0; m < 16; ++m) s += tab[(m0 + m) * KSUB + ((w[m >> 2] >> (8 * (m & 3))) & 255u)];
+                    }
+                } else {
+                    for (int m = 0; m < m_sub; ++m) s += tab[m * KSUB + code[m]];
                 }
             } else {
-                for (int m = 0; m < m_sub; ++m) s += tab[m * KSUB + code[m]];
+                bad = true;
             }
-        } else {
-            atomicOr(err, 1);
+            oq[j] = s;
         }
-        out[(size_t)q * nc + j] = s;
     }
+    if (bad) atomicOr(err, 1);
+}
+
+// Launch shape of adc_kernel: enough blocks to fill the chip several times over, each with as large a share of its
+// query's candidates as that allows.
+void adc_launch_shape(int64_t nq, int nc, int *parts, int *per_block)
+{
+    const int rounds = (nc + ADC_PER_ROUND - 1) / ADC_PER_ROUND;
+    const int64_t want_blocks = 256 * 64;  // blocks in the grid at least (when there is that much work): many short tails even out
+    int64_t p = (want_blocks + nq - 1) / nq;
+    if (p < 1) p = 1;
+    if (p > rounds) p = rounds;
+    const int rounds_per_block = (int)((rounds + p - 1) / p);
+    *per_block = rounds_per_block * ADC_PER_ROUND;
+    *parts = (rounds + rounds_per_block - 1) / rounds_per_block;
 }
 
 uint64_t splitmix64(uint64_t &st)
@@ -453,9 +495,11 @@ int leann_adc(leann_ctx *ctx, const float *queries_dev, int64_t nq, const leann_
     }
     {
         ProfScope prof(ctx, LEANN_PROF_ADC);
-        hipLaunchKernelGGL(adc_kernel, dim3((unsigned)nq, (nc + ADC_PER_BLOCK - 1) / ADC_PER_BLOCK), dim3(256), smem,
-                           ctx->stream,
-                           (const float *)ctx->s_lut.p, pq->codes, pq->n, pq->m_sub, cand_ids_dev, nc, out_dev, err);
+        int parts = 1, per_block = ADC_PER_ROUND;
+        adc_launch_shape(nq, nc, &parts, &per_block);
+        hipLaunchKernelGGL(adc_kernel, dim3((unsigned)nq, parts), dim3(256), smem, ctx->stream,
+                           (const float *)ctx->s_lut.p, pq->codes, pq->n, pq->m_sub, cand_ids_dev, nc, per_block, out_dev,
+                           err);
     }
     LEANN_HIP(hipGetLastError());
     int herr = 0;
@@ -496,8 +540,10 @@ int leann_adc_noalloc(leann_ctx *ctx, const float *queries_dev, int64_t nq, cons
     hipLaunchKernelGGL(clear_flag_kernel, dim3(1), dim3(1), 0, ctx->stream, flag);
     hipLaunchKernelGGL(lut_kernel, dim3((unsigned)nq, pq->m_sub), dim3(256), 0, ctx->stream, queries_dev, pq->d,
                        pq->m_sub, pq->codebook, lut);
-    hipLaunchKernelGGL(adc_kernel, dim3((unsigned)nq, (nc + ADC_PER_BLOCK - 1) / ADC_PER_BLOCK), dim3(256), smem,
-                       ctx->stream, (const float *)lut, pq->codes, pq->n, pq->m_sub, cand_ids_dev, nc, out_dev, flag);
+    int parts = 1, per_block = ADC_PER_ROUND;
+    adc_launch_shape(nq, nc, &parts, &per_block);
+    hipLaunchKernelGGL(adc_kernel, dim3((unsigned)nq, parts), dim3(256), smem, ctx->stream, (const float *)lut, pq->codes,
+                       pq->n, pq->m_sub, cand_ids_dev, nc, per_block, out_dev, flag);
     LEANN_HIP(hipGetLastError());
     return LEANN_OK;
 }
