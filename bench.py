@@ -125,10 +125,11 @@ def recall_at_3(ids, gt):
 
 
 def encoder_throughput(L, torch, ctx, cfg, seq=256, reps=3, batches=(32, 64, 128, 256, 512, 2048, 4096)):
-    """Config-2 style encoder-only runs: ragged batches, lengths uniform in [64, 256], uniform random token ids.
-    The headline figures are those of the largest batch; `by_batch` holds chunks/s of every batch size."""
+    """Config-2 style encoder-only runs: ragged batches, lengths uniform in [seq / 4, seq] (64 .. 256 at seq 256),
+    uniform random token ids.  The headline figures are those of the largest batch; `by_batch` holds chunks/s of
+    every batch size."""
     import leann_inputs as li
-    tokens, lengths = li.uniform_chunks(max(batches), seq, 1, cfg["vocab"], 64, seq, li.config_seed(2) + 1)
+    tokens, lengths = li.uniform_chunks(max(batches), seq, 1, cfg["vocab"], seq // 4, seq, li.config_seed(2) + 1)
     t, l = torch.from_numpy(tokens).to("cuda:0"), torch.from_numpy(lengths).to("cuda:0")
     out = torch.empty((tokens.shape[0], cfg["hidden"]), dtype=torch.float32, device="cuda:0")
     by_batch = {}
@@ -164,7 +165,8 @@ def encoder_only(args):
     ctx = L.leann_create(cfg, torch.from_numpy(w).to("cuda:0").to(torch.bfloat16))
     if args.max_tokens:
         L.leann_set_limits(ctx, args.max_tokens, 0)
-    res = encoder_throughput(L, torch, ctx, cfg, batches=(2048,) if args.profile_pass else (32, 64, 128, 256, 512, 2048, 4096))
+    res = encoder_throughput(L, torch, ctx, cfg, seq=args.enc_seq,
+                             batches=(2048 * 256 // args.enc_seq,) if args.profile_pass else (32, 64, 128, 256, 512, 2048, 4096))
     src = torch.empty(256 * 1024 * 1024, dtype=torch.float32, device="cuda:0").normal_()
     dst = torch.empty_like(src)
     dst.copy_(src)
@@ -558,7 +560,9 @@ def main():
     ap.add_argument("--encoder-only", action="store_true", help="run only the seq-256 encoder batches (profiling aid)")
     ap.add_argument("--shape", choices=["base", "small"], default="base",
                     help="BERT-base shape (12 x 768) or the 34 M-parameter 12 x 384 encoder (a second throughput point)")
-    ap.add_argument("--profile-pass", action="store_true", help="with --encoder-only: a single 2048-chunk batch")
+    ap.add_argument("--profile-pass", action="store_true",
+                    help="with --encoder-only: a single batch of 2048 chunks at seq 256 (4096 at seq 128)")
+    ap.add_argument("--enc-seq", type=int, default=256, help="with --encoder-only: padded sequence length (256 or 128)")
     ap.add_argument("--adc-microbench", action="store_true", help="run only the stand-alone ADC scorer table")
     ap.add_argument("--adc-rows", type=int, default=0, help="with --adc-microbench: a single case, table rows")
     ap.add_argument("--adc-nq", type=int, default=4096)
@@ -574,6 +578,8 @@ def main():
     ap.add_argument("--prune-M", type=int, default=64)
     ap.add_argument("--prune-m", type=int, default=16)
     ap.add_argument("--no-single-query", action="store_true")
+    ap.add_argument("--single-query-only", action="store_true",
+                    help="build the world, then only the one-query-at-a-time leg at the given --ef (the command the latency profile uses)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-encoder-bench", action="store_true")
     args = ap.parse_args()
@@ -617,6 +623,11 @@ def main():
             tot = st if tot is None else {k: tot[k] + v for k, v in st.items()}
             log(f"  queries {s0}..{min(nqs, s0 + per) - 1} done ({st['total_ms']:.0f} ms on the device)")
         return torch.cat(ids), torch.cat(scores), tot
+
+    if args.single_query_only:
+        print(json.dumps({"mode": "single-query", "n": args.n, "ef": args.ef, "rerank_ratio": args.rerank_ratio,
+                          "batch": args.batch, "single_query": single_query_leg(L, torch, world, args, args.ef)}), flush=True)
+        return
 
     # operating point: the configured ef if it reaches the target recall, else the smallest ef found by doubling
     # and bisection (the paper's protocol: minimal queue length for the target recall).  It is chosen on the tuning

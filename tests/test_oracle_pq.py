@@ -113,6 +113,20 @@ def test_permutation_is_a_seeded_permutation(orc):
     assert np.array_equal(orc.permutation(2, 0), np.array([0, 1]))
 
 
+def test_permutation_sequence_against_the_published_generator_outputs(orc):
+    """The whole sequence, not only its first draw: the generator's published outputs for state 1234567 (the test
+    vector that accompanies the public-domain splitmix64 reference code) drive a textbook Fisher-Yates shuffle of six
+    elements written out here (i from n-1 down to 1, j = draw mod (i+1), the draws in the order the generator yields
+    them); the oracle must return that permutation.  A different draw order, modulus or loop direction fails."""
+    draws = [6457827717110365317, 3203168211198807973, 9817491932198370423, 4593380528125082431, 16408922859458223821]
+    want = list(range(6))
+    for i, dr in zip(range(5, 0, -1), draws):
+        j = dr % (i + 1)
+        want[i], want[j] = want[j], want[i]
+    assert list(orc.permutation(6, 1234567)) == want
+    assert want != list(range(6))  # the case is not the identity
+
+
 def test_training_sample_is_capped(orc):
     """More rows than the training cap: still a valid codebook, built from the permutation's prefix only."""
     x = data(70000, 4, 10)
