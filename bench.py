@@ -28,12 +28,13 @@ PEAK_BF16_TFLOPS = 2500.0  # MI355X dense bf16 MFMA peak (published)
 PEAK_HBM_GBPS = 8000.0     # MI355X HBM3E peak (published)
 ADC_BYTES_PER_CANDIDATE = 40  # 32 B code row + 4 B id in, 4 B score out
 # HBM-side bytes per valid token per GEMM launch (average of the QKV, O, FFN1, FFN2 launches), from the rocprofv3
-# FETCH_SIZE / WRITE_SIZE runs summarised in profiles/encoder_seq256_hbm_traffic.md (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0
-# after calibration against a 1 GiB copy); the algorithmic minimum is 6.15 KB.
-GEMM_TRAFFIC_BYTES_PER_TOKEN = 8.96e3
+# FETCH_SIZE / WRITE_SIZE runs summarised in profiles/encoder_hbm_traffic_and_counters.md (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0
+# after calibration against a 1 GiB copy): 8.85 KB on a seq-128 pass, 8.88 KB on a seq-256 pass; the algorithmic minimum
+# is 6.15 KB.
+GEMM_TRAFFIC_BYTES_PER_TOKEN = 8.86e3
 # HBM-side bytes per ADC candidate of the 64 M-row / 4096 x 16384 launch, from the rocprofv3 read-request counters
-# (profiles/adc_microbench.md); None until measured for the kernel in the tree
-ADC_TRAFFIC_BYTES_PER_CANDIDATE = None  # set below the imports once measured
+# (profiles/adc_microbench.md): 1.094 requests of 128 bytes read + 4 bytes written
+ADC_TRAFFIC_BYTES_PER_CANDIDATE = 144.1
 
 
 def log(*a):
@@ -721,9 +722,9 @@ def main():
                      "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": gemm_tflops / PEAK_BF16_TFLOPS,
                      "traffic": GEMM_TRAFFIC_BYTES_PER_TOKEN * prof["tokens"] * cfg["layers"] * 4 / gemm_launches
                      if gemm_launches and args.shape == "base" else None,
-                     "traffic_unit": "bytes per launch, EXTRAPOLATED: bytes per token per launch from the rocprofv3 FETCH_SIZE / "
-                     "WRITE_SIZE runs of the seq-256 encoder pass (profiles/encoder_seq256_hbm_traffic.md) x tokens per "
-                     "launch of this run",
+                     "traffic_unit": "bytes per launch = bytes per token per launch from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs of "
+                     "encoder-only passes of the same kernels at seq 128 and seq 256 (8.85 / 8.88 KB, "
+                     "profiles/encoder_hbm_traffic_and_counters.md) x tokens per launch of this run",
                      "avg_launch_ms": gemm_ms / gemm_launches if gemm_launches else None,
                      "launches": gemm_launches,
                      "flops_per_launch": prof["tokens"] * gemm_flops_per_token(cfg) / gemm_launches
