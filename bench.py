@@ -64,6 +64,8 @@ def build_world(args, L, torch):
     ctx = L.leann_create(cfg, torch.from_numpy(w).to(dev).to(torch.bfloat16))
     if getattr(args, "max_tokens", 0):
         L.leann_set_limits(ctx, args.max_tokens, 0)
+    if getattr(args, "small_rows", -1) >= 0:
+        L.leann_set_gemm_tiles(ctx, 0, args.small_rows)
     del w
     space = li.make_latent_space(cfg["vocab"], seed + 1)
     last = [time.time()]
@@ -558,6 +560,8 @@ def main():
     ap.add_argument("--cache-frac", type=float, default=0.10,
                     help="extra leg: store the embeddings of this fraction of the nodes (highest degree); 0 = skip")
     ap.add_argument("--max-tokens", type=int, default=0, help="padded tokens per encoder pass (0 = library default)")
+    ap.add_argument("--small-rows", type=int, default=-1,
+                    help="passes of at most this many padded rows use the small-pass GEMM kernel (-1 = library default)")
     ap.add_argument("--encoder-only", action="store_true", help="run only the seq-256 encoder batches (profiling aid)")
     ap.add_argument("--shape", choices=["base", "small"], default="base",
                     help="BERT-base shape (12 x 768) or the 34 M-parameter 12 x 384 encoder (a second throughput point)")
