@@ -367,6 +367,28 @@ def hub_cache_leg(L, torch, world, args, ef, qps_plain, ids_plain):
             "encoded_chunks_per_query": st["encoded_chunks"] / args.nq}
 
 
+def call_memo_leg(L, torch, world, args, ef, qps_plain, ids_plain):
+    """The same step with the per-call embedding memo (leann_set_call_memo, off by default): a chunk encoded in one
+    round of the call is not encoded again in a later round.  The memo starts empty in every call, so the timed step
+    does all of its own work; the headline value is measured without it."""
+    L.leann_set_call_memo(world["ctx"], args.n)
+    try:
+        def run():
+            return L.leann_search(world["ctx"], world["queries"], world["graph"], world["pq"], world["t"], world["l"], ef,
+                                  args.k, args.rerank_ratio, args.batch)
+        run()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ids, _, st = run()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+    finally:
+        L.leann_set_call_memo(world["ctx"], 0)
+    return {"memo_rows": args.n, "memo_bytes": args.n * world["cfg"]["hidden"] * 4, "hit_rate": st["memo_hits"] / st["recomputed_chunks"],
+            "queries_per_s": args.nq / dt, "speedup": args.nq / dt / qps_plain, "same_answers": bool(torch.equal(ids, ids_plain)),
+            "encoded_chunks_per_query": st["encoded_chunks"] / args.nq, "rounds": st["rounds"]}
+
+
 def prune_ablation(args):
     """--prune-ablation: Algorithm 3 on the device against the two naive ways to shrink a graph (Sec. 5 and the ablation
     on graph pruning in Sec. 7.3): the original graph (every node may keep M edges), high-degree preserving pruning (top beta of
@@ -578,6 +600,7 @@ def main():
     ap.add_argument("--tune-margin", type=float, default=0.01,
                     help="the operating point must reach target recall + this margin on the tuning queries")
     ap.add_argument("--no-adc-leg", action="store_true")
+    ap.add_argument("--no-call-memo", action="store_true", help="skip the extra leg with the per-call embedding memo")
     ap.add_argument("--sweep", action="store_true", help="re-rank ratio x batch x ef grid on the search workload")
     ap.add_argument("--prune-ablation", action="store_true", help="graph construction variants: recall vs recomputation")
     ap.add_argument("--prune-M", type=int, default=64)
@@ -737,6 +760,8 @@ def main():
     }
     if args.cache_frac > 0:
         out["hub_cache"] = hub_cache_leg(L, torch, world, args, ef, qps, ids)
+    if not args.no_call_memo:
+        out["call_memo"] = call_memo_leg(L, torch, world, args, ef, qps, ids)
     if not args.no_single_query:
         out["single_query"] = single_query_leg(L, torch, world, args, ef)
     if not args.no_encoder_bench:

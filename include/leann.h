@@ -104,6 +104,7 @@ typedef struct {
     int64_t flushes;           /* per-query batch flushes */
     int64_t rounds;            /* traverse -> encode -> insert rounds over the whole query set */
     int64_t cache_hits;        /* exact scores served by the stored-embedding table (part of recomputed_chunks) */
+    int64_t memo_hits;         /* exact scores served by the call's embedding memo (leann_set_call_memo; part of recomputed_chunks) */
     float encoder_ms, traverse_ms, total_ms; /* device time (HIP events) */
 } leann_search_stats;
 
@@ -262,6 +263,14 @@ int leann_top_degree(leann_ctx *ctx, const uint64_t *row_ptr_dev, int64_t n, dou
 /* Tuning knobs (all optional): largest number of tokens one encoder pass holds
  * (workspace size), and the per-query capacity of the approximate queue. */
 int leann_set_limits(leann_ctx *ctx, int64_t max_tokens_per_pass, int32_t aq_capacity);
+/* Per-call embedding memo (off by default; an option for throughput with many queries per call): with max_rows > 0
+ * a leann_search call keeps up to max_rows embeddings that its own encoder passes produced (max_rows * hidden * 4 bytes
+ * of device memory plus 4 bytes per node) and serves a later request for the same chunk, by any query of the same call,
+ * from there instead of encoding it again.  The memo is empty at the start of every call: nothing computed in one call
+ * is reused in another, and nothing is stored with the index.  A chunk's embedding does not depend on its batch, so
+ * ids, scores and every per-query count are unchanged; encoded_chunks drops and memo_hits counts the requests served.
+ * Without it, requests for one chunk are merged only within a round.  max_rows = 0 turns it off and frees its memory. */
+int leann_set_call_memo(leann_ctx *ctx, int64_t max_rows);
 /* GEMM tile choice of the encoder (a tuning and test aid; results do not depend on it, every tile adds the K-slabs
  * in the same order): large_tile 256 (default) or 128 = block tile for passes of more than 8192 padded rows
  * (0 leaves it); small_rows = passes of at most this many padded rows use 64x64 tiles (default 2048). */

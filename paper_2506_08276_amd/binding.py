@@ -21,7 +21,7 @@ STATUS = {0: "LEANN_OK", -1: "LEANN_EINVAL", -2: "LEANN_ENOMEM", -3: "LEANN_EDEV
 EXPORTS = ["leann_last_error", "leann_create", "leann_destroy", "leann_embed", "leann_build_pq", "leann_pq_export",
            "leann_pq_import", "leann_pq_wrap", "leann_pq_info", "leann_pq_free", "leann_adc", "leann_adc_noalloc", "leann_search",
            "leann_search_updates", "leann_build_graph", "leann_top_degree",
-           "leann_set_limits", "leann_set_gemm_tiles", "leann_profile_begin", "leann_profile_end", "leann_bench_mfma", "leann_bench_gather"]
+           "leann_set_limits", "leann_set_call_memo", "leann_set_gemm_tiles", "leann_profile_begin", "leann_profile_end", "leann_bench_mfma", "leann_bench_gather"]
 PROF_KINDS = ["gemm_qkv", "gemm_o", "gemm_ffn1", "gemm_ffn2", "attention", "layernorm", "enc_other", "traverse",
               "collect", "score_insert", "lut", "adc"]
 
@@ -52,7 +52,8 @@ class EmbCache(C.Structure):
 class SearchStats(C.Structure):
     _fields_ = [("hops", C.c_int64), ("adc_candidates", C.c_int64), ("recomputed_chunks", C.c_int64),
                 ("encoded_chunks", C.c_int64), ("encoded_tokens", C.c_int64), ("flushes", C.c_int64),
-                ("rounds", C.c_int64), ("cache_hits", C.c_int64), ("encoder_ms", C.c_float), ("traverse_ms", C.c_float),
+                ("rounds", C.c_int64), ("cache_hits", C.c_int64), ("memo_hits", C.c_int64), ("encoder_ms", C.c_float),
+                ("traverse_ms", C.c_float),
                 ("total_ms", C.c_float)]
 
     def as_dict(self):
@@ -117,6 +118,11 @@ def leann_destroy(ctx):
 
 def leann_set_limits(ctx, max_tokens_per_pass=0, aq_capacity=0):
     _check(load_library().leann_set_limits(ctx, C.c_int64(max_tokens_per_pass), C.c_int32(aq_capacity)))
+
+
+def leann_set_call_memo(ctx, max_rows):
+    """Per-call embedding memo of leann_search: up to max_rows embeddings kept within a call (0 = off)."""
+    _check(load_library().leann_set_call_memo(ctx, C.c_int64(max_rows)))
 
 
 def leann_set_gemm_tiles(ctx, large_tile=0, small_rows=2048):

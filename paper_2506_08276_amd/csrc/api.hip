@@ -221,7 +221,7 @@ void leann_destroy(leann_ctx *ctx)
     (void)hipStreamSynchronize(ctx->stream);
     DevBuf *bufs[] = {&ctx->w_bf16, &ctx->w_f32, &ctx->x, &ctx->qkv, &ctx->att, &ctx->delta, &ctx->hid, &ctx->cu,
                       &ctx->len, &ctx->meta, &ctx->enc_ids, &ctx->s_state, &ctx->s_emb, &ctx->s_lut, &ctx->s_seen,
-                      &ctx->s_misc, &ctx->s_owner, &ctx->s_buf};
+                      &ctx->s_misc, &ctx->s_owner, &ctx->s_buf, &ctx->s_memo_slot, &ctx->s_memo_emb};
     for (DevBuf *b : bufs) b->release();
     ctx->prof_tokens.release();
     for (auto &sp : ctx->prof_spans) {
@@ -251,6 +251,20 @@ int leann_set_gemm_tiles(leann_ctx *ctx, int32_t large_tile, int32_t small_rows)
     }
     if (large_tile) ctx->gemm_large_tile = large_tile;
     ctx->gemm_small_rows = small_rows;
+    return LEANN_OK;
+}
+
+int leann_set_call_memo(leann_ctx *ctx, int64_t max_rows)
+{
+    if (!ctx || max_rows < 0) {
+        leann_set_error("leann_set_call_memo: null context or negative row count");
+        return LEANN_EINVAL;
+    }
+    ctx->memo_rows = max_rows;
+    if (max_rows == 0) {
+        ctx->s_memo_slot.release();
+        ctx->s_memo_emb.release();
+    }
     return LEANN_OK;
 }
 
@@ -369,8 +383,8 @@ int leann_search_updates(leann_ctx *ctx, const float *queries_dev, int64_t nq, c
                         (long long)graph->n, (long long)chunks->n, (long long)pq->n, pq->d, ctx->desc.hidden);
         return LEANN_ESHAPE;
     }
-    if (cache && (!cache->slot_of || !cache->emb || cache->rows < 0 || cache->rows > 0x7fffffffll)) {
-        leann_set_error("leann_search: embedding cache with null pointers or a row count outside 0..2^31-1");
+    if (cache && (!cache->slot_of || !cache->emb || cache->rows < 0 || cache->rows > (1ll << 30))) {
+        leann_set_error("leann_search: embedding cache with null pointers or a row count outside 0..2^30");
         return LEANN_EINVAL;
     }
     if (updates && (updates->buffer_n < 0 || updates->buffer_n > (1 << 24) ||

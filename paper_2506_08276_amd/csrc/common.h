@@ -65,7 +65,8 @@ struct leann_ctx {
     // encoder workspace
     DevBuf x, qkv, att, delta, hid, cu, len, meta, enc_ids;
     // search workspace
-    DevBuf s_state, s_emb, s_lut, s_seen, s_misc, s_owner, s_buf;
+    DevBuf s_state, s_emb, s_lut, s_seen, s_misc, s_owner, s_buf, s_memo_slot, s_memo_emb;
+    int64_t memo_rows = 0;  // rows of the per-call embedding memo (leann_set_call_memo), 0 = off
     // optional per-kernel timing (leann_profile_begin / leann_profile_end)
     bool prof_on = false;
     DevBuf prof_tokens;  // device int64: valid tokens sent through the encoder while profiling

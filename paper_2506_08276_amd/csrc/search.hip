@@ -28,8 +28,10 @@ struct SearchState {
     uint32_t *seen;       // [G][words]
     uint32_t *pend;       // [G][pcap]
     int32_t *n_pend;      // [G]
-    int32_t *src;         // [G][pcap]  >= 0: row of the encoder output, < 0: -(cache row + 1)
+    int32_t *src;         // [G][pcap]  >= 0: row of the encoder output; -1 .. -2^30: -(cache row + 1); below: -(2^30 + memo row + 1)
     int32_t *owner;       // [N] smallest pending entry (q * pcap + j) that asked for the chunk this round, else INT_MAX
+    int32_t *memo_slot;   // [N] row of the call's embedding memo that holds the chunk, -1: none; NULL: memo off
+    const float *memo_emb;  // [memo rows][d]
     int32_t *done;        // [G]
     int32_t *enc_off;     // [G + 1]
     int64_t *enc_ids;     // [G * pcap]
@@ -39,7 +41,8 @@ struct SearchState {
     int32_t ef, aqcap, pcap;
 };
 
-enum { CTR_HOPS = 0, CTR_ADC, CTR_RECOMP, CTR_FLUSH, CTR_PENDING, CTR_NENC, CTR_ERR, CTR_TOKENS, CTR_MAXDEG, CTR_HITS, CTR_COUNT };
+enum { CTR_HOPS = 0, CTR_ADC, CTR_RECOMP, CTR_FLUSH, CTR_PENDING, CTR_NENC, CTR_ERR, CTR_TOKENS, CTR_MAXDEG, CTR_HITS, CTR_MEMO_HITS, CTR_COUNT };
+constexpr int MEMO_SRC_BASE = 1 << 30;
 enum { ERR_BAD_NEIGHBOUR = 1, ERR_AQ_OVERFLOW = 2, ERR_P_OVERFLOW = 4, ERR_BAD_SLOT = 8 };
 
 __device__ inline bool better(float sa, uint32_t ia, float sb, uint32_t ib) { return sa > sb || (sa == sb && ia < ib); }
@@ -247,7 +250,7 @@ __global__ __launch_bounds__(64) void claim_kernel(SearchState s, const int32_t 
 {
     const int q = blockIdx.x;
     const int np = s.n_pend[q];
-    int hits = 0;
+    int hits = 0, memo_hits = 0;
     bool bad = false;
     for (int j = threadIdx.x; j < np; j += 64) {
         const uint32_t c = s.pend[(size_t)q * s.pcap + j];
@@ -256,9 +259,18 @@ __global__ __launch_bounds__(64) void claim_kernel(SearchState s, const int32_t 
             ++hits;
             continue;
         }
+        if (s.memo_slot && s.memo_slot[c] >= 0) {  // encoded earlier in this call
+            ++memo_hits;
+            continue;
+        }
         atomicMin(&s.owner[c], q * s.pcap + j);
     }
     if (bad) atomicOr((unsigned long long *)&s.counters[CTR_ERR], (unsigned long long)ERR_BAD_SLOT);
+    if (s.memo_slot) {
+        for (int o = 32; o; o >>= 1) memo_hits += __shfl_xor(memo_hits, o);
+        if (threadIdx.x == 0 && memo_hits)
+            atomicAdd((unsigned long long *)&s.counters[CTR_MEMO_HITS], (unsigned long long)memo_hits);
+    }
     if (slot_of) {
         for (int o = 32; o; o >>= 1) hits += __shfl_xor(hits, o);
         if (threadIdx.x == 0 && hits) atomicAdd((unsigned long long *)&s.counters[CTR_HITS], (unsigned long long)hits);
@@ -295,8 +307,11 @@ __global__ __launch_bounds__(1024) void collect_kernel(SearchState s, int g, con
             const int e = q * s.pcap + j;
             const uint32_t c = s.pend[e];
             const int slot = slot_of ? slot_of[c] : -1;
+            const int mslot = (slot < 0 && s.memo_slot) ? s.memo_slot[c] : -1;
             if (slot >= 0) {
                 s.src[e] = -(slot + 1);
+            } else if (mslot >= 0) {
+                s.src[e] = -(MEMO_SRC_BASE + mslot + 1);
             } else if (s.owner[c] == e) {
                 s.enc_ids[run] = c;
                 s.src[e] = run++;
@@ -319,6 +334,7 @@ __global__ __launch_bounds__(64) void resolve_kernel(SearchState s, const int32_
         const int e = q * s.pcap + j;
         const uint32_t c = s.pend[e];
         if (slot_of && slot_of[c] >= 0) continue;
+        if (s.memo_slot && s.memo_slot[c] >= 0) continue;
         const int o = s.owner[c];
         if (o != e) s.src[e] = s.src[o];
     }
@@ -350,7 +366,9 @@ __global__ __launch_bounds__(64) void score_insert_kernel(SearchState s, const f
     for (int c = 0; c < np; ++c) {
         const int src = s.src[(size_t)q * s.pcap + c];
         const uint32_t id = s.pend[(size_t)q * s.pcap + c];
-        const float *e = src >= 0 ? enc_emb + (size_t)src * d : cache_emb + (size_t)(-src - 1) * d;
+        const float *e = src >= 0                ? enc_emb + (size_t)src * d
+                         : src >= -MEMO_SRC_BASE ? cache_emb + (size_t)(-src - 1) * d
+                                                 : s.memo_emb + (size_t)(-(src + MEMO_SRC_BASE) - 1) * d;
         float acc = 0.f;
 #pragma unroll
         for (int j = 0; j < 16; ++j)
@@ -395,6 +413,20 @@ __global__ __launch_bounds__(64) void score_insert_kernel(SearchState s, const f
         atomicAdd((unsigned long long *)&s.counters[CTR_RECOMP], (unsigned long long)np);
         atomicAdd((unsigned long long *)&s.counters[CTR_FLUSH], 1ull);
     }
+}
+
+// The call's embedding memo: rows the encoder produced in this round are kept (while there is room) so that a later
+// round of the same call reads them instead of encoding the chunk again.  One wavefront per encoded chunk.
+__global__ __launch_bounds__(256) void memo_store_kernel(const float *__restrict__ enc_emb, const int64_t *__restrict__ enc_ids,
+                                                         int n_enc, int d, int64_t base, int64_t cap,
+                                                         float *__restrict__ memo_emb, int32_t *__restrict__ memo_slot)
+{
+    const int i = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (i >= n_enc || base + i >= cap) return;
+    const float *srcp = enc_emb + (size_t)i * d;
+    float *dst = memo_emb + (size_t)(base + i) * d;
+    for (int c = lane; c < d; c += 64) dst[c] = srcp[c];
+    if (lane == 0) memo_slot[enc_ids[i]] = (int32_t)(base + i);
 }
 
 // Exact scores of the add buffer (App. B "Batched Add Operation": buffered chunks are scanned, not traversed):
@@ -524,6 +556,14 @@ int search_run(leann_ctx *ctx, const float *queries_dev, int64_t nq, const leann
     LEANN_TRY(ctx->s_emb.reserve((size_t)G * pcap * d * sizeof(float)));
     LEANN_TRY(ctx->s_owner.reserve((size_t)n * sizeof(int32_t)));
     LEANN_HIP(hipMemsetAsync(ctx->s_owner.p, 0x7f, (size_t)n * sizeof(int32_t), st));
+    // per-call embedding memo (leann_set_call_memo): empty at the start of every call
+    const int64_t memo_cap = std::min<int64_t>(ctx->memo_rows, MEMO_SRC_BASE - 1);
+    int64_t memo_n = 0;
+    if (memo_cap > 0) {
+        LEANN_TRY(ctx->s_memo_slot.reserve((size_t)n * sizeof(int32_t)));
+        LEANN_TRY(ctx->s_memo_emb.reserve((size_t)memo_cap * d * sizeof(float)));
+        LEANN_HIP(hipMemsetAsync(ctx->s_memo_slot.p, 0xff, (size_t)n * sizeof(int32_t), st));
+    }
     char *base = (char *)ctx->s_state.p;
     SearchState s;
     s.eq_score = (float *)(base + o_eqs);
@@ -539,6 +579,8 @@ int search_run(leann_ctx *ctx, const float *queries_dev, int64_t nq, const leann
     s.src = (int32_t *)(base + o_src);
     s.done = (int32_t *)(base + o_done);
     s.owner = (int32_t *)ctx->s_owner.p;
+    s.memo_slot = memo_cap > 0 ? (int32_t *)ctx->s_memo_slot.p : nullptr;
+    s.memo_emb = memo_cap > 0 ? (const float *)ctx->s_memo_emb.p : nullptr;
     s.enc_off = (int32_t *)(base + o_eoff);
     s.enc_ids = (int64_t *)(base + o_eids);
     s.counters = counters;
@@ -615,6 +657,12 @@ int search_run(leann_ctx *ctx, const float *queries_dev, int64_t nq, const leann
                                  (int64_t *)&counters[CTR_TOKENS]);
                 if (rc != LEANN_OK) break;
                 encoded += n_enc;
+                if (memo_cap > 0 && memo_n < memo_cap) {
+                    hipLaunchKernelGGL(memo_store_kernel, dim3((unsigned)((n_enc + 3) / 4)), dim3(256), 0, st,
+                                       (const float *)ctx->s_emb.p, s.enc_ids, (int)n_enc, d, memo_n, memo_cap,
+                                       (float *)ctx->s_memo_emb.p, s.memo_slot);
+                    memo_n = std::min<int64_t>(memo_cap, memo_n + n_enc);
+                }
             }
             {
                 ProfScope prof(ctx, LEANN_PROF_SCORE_INSERT);
@@ -661,6 +709,7 @@ int search_run(leann_ctx *ctx, const float *queries_dev, int64_t nq, const leann
         stats->adc_candidates = h_ctr[CTR_ADC];
         stats->recomputed_chunks = h_ctr[CTR_RECOMP];
         stats->cache_hits = h_ctr[CTR_HITS];
+        stats->memo_hits = h_ctr[CTR_MEMO_HITS];
         stats->encoded_chunks = encoded;
         stats->encoded_tokens = h_ctr[CTR_TOKENS];
         stats->flushes = h_ctr[CTR_FLUSH];

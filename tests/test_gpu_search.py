@@ -117,6 +117,46 @@ def test_hub_embedding_cache_changes_work_not_results(L, world):
           f"{st0['encoded_chunks']} -> {st1['encoded_chunks']}")
 
 
+def test_call_memo_changes_work_not_results(L, world):
+    """The per-call embedding memo (leann_set_call_memo): a chunk that one round of a call has encoded is not encoded
+    again by a later round of the same call.  Ids, scores and every per-query count are those of the plain search;
+    only encoded_chunks drops.  A memo that is too small to hold everything, and a second call (the memo starts
+    empty), behave the same way."""
+    import torch
+    w = world
+    args = (w["graph"], w["pq"], w["t"], w["l"], 32, 3, 0.2, 32)
+    ids0, sc0, st0 = L.leann_search(w["ctx"], w["q"], *args)
+    assert st0["memo_hits"] == 0
+    try:
+        for rows in (w["n"], 40):
+            say(f"call memo of {rows} rows")
+            L.leann_set_call_memo(w["ctx"], rows)
+            for _ in range(2):  # the second call starts from an empty memo again: same totals
+                ids1, sc1, st1 = L.leann_search(w["ctx"], w["q"], *args)
+                assert torch.equal(ids0, ids1) and torch.equal(sc0, sc1)
+                for key in ("hops", "adc_candidates", "recomputed_chunks", "flushes", "rounds"):
+                    assert st0[key] == st1[key], key
+                assert st1["memo_hits"] > 0 and st1["encoded_chunks"] < st0["encoded_chunks"]
+                if rows == w["n"]:
+                    full = dict(st1)
+                else:
+                    assert st1["memo_hits"] < full["memo_hits"]  # 40 rows hold less than everything
+            print(f"call memo {rows} rows: encoded chunks {st0['encoded_chunks']} -> {st1['encoded_chunks']}, "
+                  f"{st1['memo_hits']} of {st1['recomputed_chunks']} requests served by the memo")
+        # together with a stored-embedding table: table first, memo for the rest
+        ids_hub, slot_of = li.hub_slots(w["row_ptr"], w["col_idx"], 0.10)
+        rows = L.leann_embed(w["ctx"], w["t"], w["l"], hidden=w["cfg"]["hidden"], ids=to_dev(ids_hub))
+        L.leann_set_call_memo(w["ctx"], w["n"])
+        ids2, sc2, st2 = L.leann_search(w["ctx"], w["q"], *args, cache=(to_dev(slot_of), rows))
+        assert torch.equal(ids0, ids2) and torch.equal(sc0, sc2)
+        assert st2["cache_hits"] > 0 and st2["memo_hits"] > 0
+        assert st2["encoded_chunks"] < full["encoded_chunks"]
+    finally:
+        L.leann_set_call_memo(w["ctx"], 0)
+    ids3, sc3, st3 = L.leann_search(w["ctx"], w["q"], *args)
+    assert torch.equal(ids0, ids3) and st3["memo_hits"] == 0 and st3["encoded_chunks"] == st0["encoded_chunks"]
+
+
 def pack_bits(flags):
     """uint8 flags [n] -> int32 words, bit (v & 31) of word (v >> 5)."""
     n = len(flags)
