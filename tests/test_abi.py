@@ -46,3 +46,38 @@ def test_oracle_is_not_imported_by_the_product():
             if f.endswith((".py", ".hip", ".h", ".cpp")):
                 src = open(os.path.join(base, f)).read()
                 assert "oracle" not in src.lower() or f == "binding.py" and False, f
+
+
+def test_argument_checks_need_no_gpu():
+    """Calls that validate their arguments before touching the device: null handles and out-of-range values come back
+    as LEANN_EINVAL with a message, on a machine without a GPU too."""
+    import paper_2506_08276_amd as L
+    if not os.path.exists(L.LIB_PATH):
+        pytest.skip("libleann.so not built (run __graft_entry__.build())")
+    lib = ctypes.CDLL(L.LIB_PATH)
+    lib.leann_last_error.restype = ctypes.c_char_p
+    null = ctypes.c_void_p(None)
+    EINVAL = -1
+    calls = [
+        lambda: lib.leann_set_limits(null, ctypes.c_int64(0), ctypes.c_int32(0)),
+        lambda: lib.leann_set_gemm_tiles(null, ctypes.c_int32(0), ctypes.c_int32(0)),
+        lambda: lib.leann_set_call_memo(null, ctypes.c_int64(1)),
+        lambda: lib.leann_pq_info(null, null, null, null),
+        lambda: lib.leann_profile_begin(null),
+        lambda: lib.leann_profile_end(null, null),
+        lambda: lib.leann_embed(null, null, null, ctypes.c_int64(1), null),
+        lambda: lib.leann_adc(null, null, ctypes.c_int64(1), null, null, ctypes.c_int32(1), null),
+        lambda: lib.leann_adc_noalloc(null, null, ctypes.c_int64(1), null, null, ctypes.c_int32(1), null),
+        lambda: lib.leann_build_pq(null, null, ctypes.c_int64(1), ctypes.c_int32(8), ctypes.c_int32(1), ctypes.c_int32(1),
+                                   ctypes.c_uint64(0), null),
+        lambda: lib.leann_search(null, null, ctypes.c_int64(1), null, null, null, null, ctypes.c_int32(4), ctypes.c_int32(1),
+                                 ctypes.c_float(0.5), ctypes.c_int32(1), null, null, null),
+        lambda: lib.leann_bench_mfma(null, ctypes.c_int32(0), ctypes.c_int32(1), ctypes.c_int32(1), ctypes.c_int32(1), null, null),
+        lambda: lib.leann_bench_gather(null, null, ctypes.c_int64(1), ctypes.c_int32(1), null, null),
+        lambda: lib.leann_create(null, null, null, ctypes.c_int(0), ctypes.c_int(0), null),
+    ]
+    for call in calls:
+        assert call() == EINVAL
+        assert len(lib.leann_last_error(None)) > 0
+    lib.leann_destroy(null)   # no-ops on null handles
+    lib.leann_pq_free(null)

@@ -29,6 +29,10 @@ MISTAKES = [
     ("enc", "softmax numerator shifted", "p[j] = expf(p[j] - mx);", "p[j] = expf(p[j] - mx) + 1e-3f;"),
     # PQ / ADC
     ("pq", "look-up table without the negation", "lut[m * ksub + c] = -s;", "lut[m * ksub + c] = s;"),
+    ("pq", "shuffle draws modulo i instead of i + 1", "uint64_t j = splitmix64(&st) % (uint64_t)(i + 1);",
+     "uint64_t j = splitmix64(&st) % (uint64_t)i;"),
+    ("pq", "shuffle walks upwards", "for (int64_t i = n - 1; i >= 1; --i) {\n        uint64_t j = splitmix64(&st)",
+     "for (int64_t i = 1; i <= n - 1; ++i) {\n        uint64_t j = splitmix64(&st)"),
     # search
     ("search", "ties broken towards the higher id", "return sa > sb || (sa == sb && ia < ib);",
      "return sa > sb || (sa == sb && ia > ib);"),
