@@ -285,6 +285,11 @@ def mfma_peak_mode(args):
             tf, ms = L.leann_bench_mfma(ctx, kind, blocks_per_cu=bpc, iters=4000, launches=60)
             print(json.dumps({"mode": "mfma-peak", "operands": name, "waves_per_cu": 4 * bpc, "tflops": tf,
                               "frac_of_published_peak": tf / PEAK_BF16_TFLOPS, "ms_per_launch": ms}), flush=True)
+    # operand-feed ceiling: the GEMM's load pattern alone, from L2 and from memory
+    for rows, where in ((2048, "3 MB panel (L2 resident)"), (200000, "307 MB panel (from memory)")):
+        bps, ms = L.leann_bench_l1pull(ctx, rows, launches=5)
+        print(json.dumps({"mode": "mfma-peak", "operand_feed": where, "TBps": bps / 1e12,
+                          "bytes_per_clk_per_cu_at_2.1GHz": bps / 256 / 2.1e9, "ms_per_launch": ms}), flush=True)
     L.leann_destroy(ctx)
 
 

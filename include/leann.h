@@ -316,6 +316,14 @@ int leann_bench_mfma(leann_ctx *ctx, int32_t operand_kind, int32_t blocks_per_cu
 int leann_bench_gather(leann_ctx *ctx, const uint8_t *table_dev, int64_t table_rows, int32_t launches,
                        double *rows_per_s_host, double *ms_host);
 
+/*
+ * Measured ceiling of the GEMM's operand feed (benchmark hook): one block of eight waves per compute unit does nothing
+ * but the GEMM's operand loads (16 bytes per lane, 64-byte row pieces of 1536-byte rows, eight in flight per lane) over
+ * a panel of panel_rows rows allocated inside the call: a panel of a few MB is served by the L2, a large one by memory.
+ * bytes_per_s_host receives the rate over `launches` timed launches after one warm-up launch.  Synchronises.
+ */
+int leann_bench_l1pull(leann_ctx *ctx, int64_t panel_rows, int32_t launches, double *bytes_per_s_host, double *ms_host);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,7 +21,7 @@ STATUS = {0: "LEANN_OK", -1: "LEANN_EINVAL", -2: "LEANN_ENOMEM", -3: "LEANN_EDEV
 EXPORTS = ["leann_last_error", "leann_create", "leann_destroy", "leann_embed", "leann_build_pq", "leann_pq_export",
            "leann_pq_import", "leann_pq_wrap", "leann_pq_info", "leann_pq_free", "leann_adc", "leann_adc_noalloc", "leann_search",
            "leann_search_updates", "leann_build_graph", "leann_top_degree",
-           "leann_set_limits", "leann_set_call_memo", "leann_set_gemm_tiles", "leann_profile_begin", "leann_profile_end", "leann_bench_mfma", "leann_bench_gather"]
+           "leann_set_limits", "leann_set_call_memo", "leann_set_gemm_tiles", "leann_profile_begin", "leann_profile_end", "leann_bench_mfma", "leann_bench_gather", "leann_bench_l1pull"]
 PROF_KINDS = ["gemm_qkv", "gemm_o", "gemm_ffn1", "gemm_ffn2", "attention", "layernorm", "enc_other", "traverse",
               "collect", "score_insert", "lut", "adc"]
 
@@ -339,3 +339,10 @@ def leann_bench_gather(ctx, table, launches=5):
     _check(load_library().leann_bench_gather(ctx, _ptr(table), C.c_int64(table.shape[0]), C.c_int32(launches),
                                              C.byref(rps), C.byref(ms)))
     return rps.value, ms.value
+
+
+def leann_bench_l1pull(ctx, panel_rows, launches=5):
+    """(bytes/s, ms per launch) of eight waves per CU doing only the GEMM's operand loads over a panel of 1536-byte rows."""
+    bps, ms = C.c_double(), C.c_double()
+    _check(load_library().leann_bench_l1pull(ctx, C.c_int64(panel_rows), C.c_int32(launches), C.byref(bps), C.byref(ms)))
+    return bps.value, ms.value

@@ -87,7 +87,80 @@ __global__ void peak_ids_kernel(uint32_t *ids, size_t n, uint32_t rows)
     }
 }
 
+// Operand-feed ceiling of the GEMM: what a CU's vector L1 delivers when eight waves do nothing but the GEMM's operand
+// loads.  A block of 512 threads walks the columns of a 256-row window of a panel of 1536-byte rows (K = 768 bf16) with
+// 16-byte loads, four lanes per 64-byte row piece as in the GEMM, eight loads in flight per lane; the words are folded
+// into one value per thread so that the loads are live.  A small panel stays in the XCDs' L2 (the windows of the blocks
+// overlap), a large one comes from memory.
+__global__ __launch_bounds__(512) void peak_pull_kernel(const unsigned char *__restrict__ panel, int rows, int iters,
+                                                        uint32_t *__restrict__ out)
+{
+    constexpr int ROWB = 1536, PIECE = 64, LPR = PIECE / 16, RPI = 512 / LPR, AHEAD = 8;
+    const int tid = threadIdx.x, r = tid / LPR, c = tid % LPR;
+    const int row_base = (int)((blockIdx.x * 64u) % (unsigned)(rows - 256 - RPI));
+    uint32_t acc = 0;
+    for (int it = 0; it < iters; ++it) {
+        u32x4 v[AHEAD];
+#pragma unroll
+        for (int j = 0; j < AHEAD; ++j) {
+            const int step = it * AHEAD + j;
+            const int col = (step % (ROWB / PIECE)) * PIECE;
+            const int rr = row_base + ((step / (ROWB / PIECE)) * RPI + r) % 256;
+            v[j] = *reinterpret_cast<const u32x4 *>(panel + (size_t)rr * ROWB + col + c * 16);
+        }
+#pragma unroll
+        for (int j = 0; j < AHEAD; ++j) acc ^= v[j][0] ^ v[j][1] ^ v[j][2] ^ v[j][3];
+    }
+    out[(size_t)blockIdx.x * 512 + tid] = acc;
+}
+
 }  // namespace
+
+extern "C" int leann_bench_l1pull(leann_ctx *ctx, int64_t panel_rows, int32_t launches, double *bytes_per_s_host,
+                                  double *ms_host)
+{
+    if (!ctx || !bytes_per_s_host || panel_rows < 1024 || panel_rows > (1 << 22) || launches < 1 || launches > 1000) {
+        leann_set_error("leann_bench_l1pull: null argument, panel rows outside 1024..2^22, or launch count outside 1..1000");
+        return LEANN_EINVAL;
+    }
+    LEANN_HIP(hipSetDevice(ctx->device));
+    const int grid = ctx->num_cus, iters = 2000;
+    DevBuf panel, out;
+    int rc = panel.reserve((size_t)panel_rows * 1536);
+    if (rc == LEANN_OK) rc = out.reserve((size_t)grid * 512 * sizeof(uint32_t));
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (rc == LEANN_OK && (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess)) {
+        leann_set_error("leann_bench_l1pull: event creation failed");
+        rc = LEANN_EDEVICE;
+    }
+    float ms = 0.f;
+    if (rc == LEANN_OK) {
+        hipStream_t st = ctx->stream;
+        hipError_t e = hipMemsetAsync(panel.p, 1, (size_t)panel_rows * 1536, st);
+        hipLaunchKernelGGL(peak_pull_kernel, dim3(grid), dim3(512), 0, st, (const unsigned char *)panel.p, (int)panel_rows,
+                           iters, (uint32_t *)out.p);
+        (void)hipEventRecord(e0, st);
+        for (int l = 0; l < launches; ++l)
+            hipLaunchKernelGGL(peak_pull_kernel, dim3(grid), dim3(512), 0, st, (const unsigned char *)panel.p,
+                               (int)panel_rows, iters, (uint32_t *)out.p);
+        (void)hipEventRecord(e1, st);
+        if (e == hipSuccess) e = hipGetLastError();
+        if (e == hipSuccess) e = hipStreamSynchronize(st);
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+        if (e != hipSuccess) {
+            leann_set_error("leann_bench_l1pull: %s", hipGetErrorString(e));
+            rc = LEANN_EDEVICE;
+        }
+    }
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    panel.release();
+    out.release();
+    if (rc != LEANN_OK) return rc;
+    *bytes_per_s_host = (double)grid * 512 * 16.0 * iters * 8 * launches / (ms * 1e-3);
+    if (ms_host) *ms_host = ms / launches;
+    return LEANN_OK;
+}
 
 extern "C" int leann_bench_gather(leann_ctx *ctx, const uint8_t *table_dev, int64_t table_rows, int32_t launches,
                                   double *rows_per_s_host, double *ms_host)

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def declared_symbols():
     text = open(os.path.join(ROOT, "include", "leann.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(leann_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(leann_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_header_declares_the_north_star_calls():
