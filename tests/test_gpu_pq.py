@@ -67,6 +67,35 @@ def test_adc_matches_oracle(L, orc, ctx, d, m_sub, n, nc):
     L.leann_pq_free(pq)
 
 
+@pytest.mark.parametrize("m_sub,d", [(32, 768), (16, 128)])
+def test_adc_many_queries_several_rounds_per_block(L, orc, ctx, m_sub, d):
+    """Launch shapes in which a block of the scorer goes through several rounds of 2048 candidates with its lookup
+    table kept in LDS, and a query's candidates are split over several blocks (9000 queries x 4100 candidates: two
+    blocks per query, two rounds in the first, a ragged one in the second): sampled queries against the oracle, and
+    the whole result against the same candidates scored 1500 at a time (one round per block)."""
+    import torch
+    n, nq, nc = 5000, 9000, 4100
+    say(f"adc multi-round d={d} m_sub={m_sub} nq={nq} nc={nc}")
+    x = unit_rows(n, d, 3)
+    cb, _ = orc.pq_train(x, m_sub, 2, 5)
+    codes = orc.pq_encode(x, cb)
+    pq = L.leann_pq_import(ctx, cb, codes)
+    queries = unit_rows(nq, d, 8)
+    g = torch.Generator(device="cpu").manual_seed(5)
+    cand = torch.randint(0, n, (nq, nc), dtype=torch.int32, generator=g)
+    qd, cd = to_dev(queries), cand.to("cuda:0")
+    got = L.leann_adc(ctx, qd, pq, cd)
+    for s0 in range(0, nc, 1500):
+        part = L.leann_adc(ctx, qd, pq, cd[:, s0:s0 + 1500].contiguous())
+        assert torch.equal(got[:, s0:s0 + 1500], part), s0
+    got = got.cpu().numpy()
+    cand = cand.numpy().view(np.uint32)
+    for qi in (0, 4499, 8999):
+        want, l1 = orc.adc(orc.lut(queries[qi], cb), codes, cand[qi])
+        assert np.all(np.abs(got[qi] - want) <= 1e-4 * np.maximum(np.abs(want), l1))
+    L.leann_pq_free(pq)
+
+
 @pytest.mark.parametrize("n,d,m_sub,iters", [(2000, 128, 16, 10), (70000, 48, 2, 3)])
 def test_build_pq_invariants_and_error(L, orc, ctx, n, d, m_sub, iters):
     say(f"build_pq n={n} d={d} m_sub={m_sub} iters={iters}")
