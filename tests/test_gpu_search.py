@@ -157,6 +157,25 @@ def test_call_memo_changes_work_not_results(L, world):
     assert torch.equal(ids0, ids3) and st3["memo_hits"] == 0 and st3["encoded_chunks"] == st0["encoded_chunks"]
 
 
+def test_queue_capacity_overflow_is_reported(L, world):
+    """An approximate queue that outgrows its capacity (set far too small through leann_set_limits) ends the search
+    with LEANN_ECAPACITY: the kernel's own bounds checks drop the entries that do not fit and raise the flag."""
+    import torch
+    w = world
+    args = (w["graph"], w["pq"], w["t"], w["l"], 32, 3, 0.2, 32)
+    ids0, sc0, _ = L.leann_search(w["ctx"], w["q"], *args, cache=w["full_cache"])
+    say("AQ capacity 8 (overflow expected)")
+    L.leann_set_limits(w["ctx"], 0, 8)
+    try:
+        with pytest.raises(L.LeannError) as ei:
+            L.leann_search(w["ctx"], w["q"], *args, cache=w["full_cache"])
+        assert ei.value.status == -5
+    finally:
+        L.leann_set_limits(w["ctx"], 0, 32768)
+    ids1, sc1, _ = L.leann_search(w["ctx"], w["q"], *args, cache=w["full_cache"])
+    assert torch.equal(ids0, ids1) and torch.equal(sc0, sc1)
+
+
 def pack_bits(flags):
     """uint8 flags [n] -> int32 words, bit (v & 31) of word (v >> 5)."""
     n = len(flags)
